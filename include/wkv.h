@@ -1,0 +1,194 @@
+/*
+ * wkv.h — C ABI of the MI355X (gfx950) WindowKV prefill-time KV-cache window selection.
+ *
+ * The library computes, for one batch of sequences and one or more layer groups, what
+ * Section 2.2 of the WindowKV paper (arXiv 2503.17922) defines:
+ *
+ *   Eq. 1   A = softmax(Q K^T / sqrt(d_k))           causal, over the whole prefix
+ *   Eq. 2   t_j = sum_{i in last w_obs rows} A_ij      j in the review context [0, L - w_obs)
+ *           (summed also over the G = Hq/Hkv query heads that share a KV head)
+ *   Eq. 3   review windows W_k of `win` consecutive tokens (the last may be partial)
+ *   Eq. 4   s_k = sum(Top-p(W_k)) / min(p, win)
+ *   2.2.1   keep the k highest-scoring windows plus the last w_obs tokens
+ *   2.2.2   the first layer of a group is scored; every layer of the group keeps the rows
+ *           at those indices.
+ *
+ * Notation: L = prefix length (paper: n), w_obs = observation window (alpha), win = review
+ * window size (omega), p = top_p, gamma = layers per group, NW = ceil((L - w_obs)/win).
+ *
+ * Conventions common to every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are read
+ *     during the call only and may be freed on return.
+ *   - Work is enqueued on the caller's hipStream_t (passed as void*; NULL = default stream).
+ *     Calls return without synchronising; results are valid in stream order.
+ *   - The library allocates nothing, frees nothing and keeps no device state between calls.
+ *   - Every argument is validated on the host before the first launch; a failed validation
+ *     launches nothing.  Errors come back as wkv_status; nothing is thrown.
+ *   - All index outputs are int32.  Tensors are addressed with 64-bit offsets.
+ */
+#ifndef WKV_H
+#define WKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WKV_MAX_BATCH      64     /* sequences per call                                   */
+#define WKV_MAX_GROUPS     64     /* layer groups per wkv_compress_groups call            */
+#define WKV_MAX_LAYERS     64     /* layers per wkv_gather_group / wkv_compress_groups    */
+#define WKV_MAX_WIN        128    /* largest review-window size                           */
+#define WKV_MAX_OBS_ROWS   256    /* largest G * w_obs                                    */
+#define WKV_MAX_WINDOWS    32768  /* largest NW of any sequence                           */
+
+typedef enum {
+  WKV_OK = 0,
+  WKV_ERR_INVALID_ARG = -1,   /* null pointer, inconsistent sizes, out-of-range parameter */
+  WKV_ERR_UNSUPPORTED = -2,   /* valid problem outside the limits above / dtype / head_dim */
+  WKV_ERR_WORKSPACE   = -3,   /* workspace missing, misaligned or too small                */
+  WKV_ERR_HIP         = -4    /* a HIP call or kernel launch failed                        */
+} wkv_status;
+
+typedef enum { WKV_F32 = 0, WKV_BF16 = 1 } wkv_dtype;
+
+/*
+ * One batch of sequences.  The same description serves one layer group or several (the
+ * per-sequence parameters are shared by all groups of a call).
+ *
+ * Tensor layouts (strides in ELEMENTS; the head_dim axis always has stride 1):
+ *   q_obs   [batch, n_q_heads,  w_obs,       head_dim]   the last w_obs query vectors of the
+ *                                                         scored layer, positions L-w_obs..L-1
+ *   K, V    [batch, n_kv_heads, max_seq_len, head_dim]   full cache of one layer; sequence b
+ *                                                         uses token rows 0 .. seq_len[b]-1
+ *   K_out,
+ *   V_out   [batch, n_kv_heads, nkeep_max,   head_dim]   compact cache of one layer
+ * Query head hq belongs to KV head hq / (n_q_heads / n_kv_heads).
+ */
+typedef struct {
+  int32_t batch;             /* 1 .. WKV_MAX_BATCH                                        */
+  int32_t n_q_heads;         /* Hq, multiple of n_kv_heads                                */
+  int32_t n_kv_heads;        /* Hkv                                                       */
+  int32_t head_dim;          /* d: 64 or 128                                              */
+  int32_t w_obs;             /* alpha, >= 1; (Hq/Hkv) * w_obs <= WKV_MAX_OBS_ROWS          */
+  int32_t max_seq_len;       /* token capacity of the K/V tensors, >= every seq_len[b]    */
+  int32_t dtype;             /* wkv_dtype of q_obs, K, V and the compact cache            */
+  float   scale;             /* logit scale; 0 selects 1/sqrt(head_dim) (Eq. 1)           */
+  const int32_t *seq_len;    /* host [batch]  L_b,   w_obs <= L_b <= max_seq_len          */
+  const int32_t *win;        /* host [batch]  omega, 1 .. WKV_MAX_WIN                     */
+  const int32_t *top_p;      /* host [batch]  p, >= 1 (p >= win means the window mean)    */
+  const int32_t *k_windows;  /* host [batch]  windows to keep, 0 .. NW_b                  */
+  int64_t q_stride_b, q_stride_h, q_stride_t;        /* q_obs                             */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_t;     /* full K and V (same for both)      */
+  int64_t out_stride_b, out_stride_h, out_stride_t;  /* compact K_out and V_out           */
+} wkv_problem;
+
+/* Sizes derived from a problem; every output buffer below is sized by these. */
+typedef struct {
+  int32_t obs_rows;      /* (Hq/Hkv) * w_obs : softmax rows per KV head                   */
+  int32_t t_stride;      /* max_seq_len - w_obs : row length of the token-score array     */
+  int32_t nw_max;        /* max_b NW_b          : row length of the window-score array    */
+  int32_t k_max;         /* max_b k_windows[b]  : row length of win_idx                   */
+  int32_t nkeep_max;     /* max_b k_b*win_b + w_obs : row length of tok_idx, rows of K_out */
+  int64_t total_tokens;  /* sum_b L_b                                                     */
+} wkv_dims;
+
+/* Validates the problem (host only, no GPU needed) and fills *dims. */
+wkv_status wkv_get_dims(const wkv_problem *problem, wkv_dims *dims);
+
+/* Bytes of device workspace the calls below need for `n_groups` groups (n_groups = 1 for
+ * the per-stage calls).  Returns 0 for an invalid problem.  The workspace must be 256-byte
+ * aligned; its contents on entry are irrelevant and on return unspecified. */
+size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups);
+
+/*
+ * Eq. 1-2: token scores of one layer group.
+ *   q_obs   device, layout above
+ *   k_first device, K of the group's first layer
+ *   t_out   device float32 [batch, n_kv_heads, t_stride]; entries j < L_b - w_obs are written,
+ *           the rest of each row is set to 0.
+ * The softmax runs in fp32 on fp32-accumulated logits; no exponent is taken of an
+ * unshifted logit, so any finite inputs are safe.
+ */
+wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *k_first,
+                     float *t_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Eq. 3-4: window scores.
+ *   t      device float32 [batch, n_kv_heads, t_stride]
+ *   s_out  device float32 [batch, n_kv_heads, nw_max]; entries w < NW_b are written, the rest
+ *          of each row is set to -inf.
+ * A partial last window takes the min(p, size) largest of the tokens it has and keeps the
+ * divisor min(p, win).
+ */
+wkv_status wkv_window_pool(const wkv_problem *problem, const float *t, float *s_out,
+                           void *hip_stream);
+
+/*
+ * Section 2.2.1, selection: the k_windows[b] highest-scoring windows of every (b, KV head),
+ * equal scores resolved towards the lower window index, reported in ascending order, and the
+ * retained token positions: all tokens of the selected windows followed by L_b-w_obs .. L_b-1.
+ *   s            device float32 [batch, n_kv_heads, nw_max]
+ *   win_idx_out  device int32   [batch, n_kv_heads, k_max]      ascending, padded with -1
+ *   tok_idx_out  device int32   [batch, n_kv_heads, nkeep_max]  ascending, padded with -1
+ *   n_keep_out   device int32   [batch, n_kv_heads]             valid entries of tok_idx
+ * (n_keep is k*win + w_obs, less the missing tokens of a selected partial last window.)
+ */
+wkv_status wkv_topk_windows(const wkv_problem *problem, const float *s, int32_t *win_idx_out,
+                            int32_t *tok_idx_out, int32_t *n_keep_out, void *hip_stream);
+
+/*
+ * Section 2.2.2: every layer of a group keeps the rows at the group's shared indices.
+ *   n_layers               1 .. WKV_MAX_LAYERS
+ *   k_layers, v_layers     host arrays [n_layers] of device pointers to full K / V
+ *   tok_idx, n_keep        device, as written by wkv_topk_windows
+ *   k_out_layers,
+ *   v_out_layers           host arrays [n_layers] of device pointers to compact K_out / V_out
+ * Row r < n_keep[b,h] of an output is a bit-exact copy of input row tok_idx[b,h,r]; rows
+ * n_keep[b,h] .. nkeep_max-1 are zero-filled.  Inputs and outputs must not overlap.
+ */
+wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
+                            const void *const *k_layers, const void *const *v_layers,
+                            const int32_t *tok_idx, const int32_t *n_keep,
+                            void *const *k_out_layers, void *const *v_out_layers,
+                            void *hip_stream);
+
+/*
+ * The whole path (Eq. 1-4, selection, sharing, gather) for n_groups layer groups of gamma
+ * layers each, batched so that every stage is one launch over all groups.
+ *   q_obs_groups   host array [n_groups] of device pointers: q_obs of each group's first layer
+ *   k_layers, v_layers, k_out_layers, v_out_layers
+ *                  host arrays [n_groups*gamma] of device pointers, layer l of group g at
+ *                  index g*gamma + l; group g is scored on k_layers[g*gamma] only
+ *   win_idx_out    device int32 [n_groups, batch, n_kv_heads, k_max]
+ *   tok_idx_out    device int32 [n_groups, batch, n_kv_heads, nkeep_max]
+ *   n_keep_out     device int32 [n_groups, batch, n_kv_heads]
+ * Results are identical to running the four stage calls group by group.
+ * n_groups <= WKV_MAX_GROUPS, n_groups*gamma <= WKV_MAX_LAYERS.
+ */
+wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                               const void *const *q_obs_groups,
+                               const void *const *k_layers, const void *const *v_layers,
+                               void *const *k_out_layers, void *const *v_out_layers,
+                               int32_t *win_idx_out, int32_t *tok_idx_out, int32_t *n_keep_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Section 2.2.3, Eq. 5-7 (host only): arithmetic-sequence budgets for n_groups groups,
+ * b^{H-1} = b_total/(lambda*H), b^0 = 2*b_total/H - b^{H-1}, linear in between.
+ *   budgets_out  host double [n_groups], real-valued as in the paper; turning a budget into
+ *                a whole number of windows is left to the caller.
+ */
+wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
+                             double *budgets_out);
+
+const char *wkv_status_string(wkv_status status);
+
+/* Message describing the most recent failure on the calling thread ("" if none). */
+const char *wkv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WKV_H */

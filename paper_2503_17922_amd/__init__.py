@@ -1,0 +1,199 @@
+"""Thin Python binding of libwkv (MI355X WindowKV window selection).
+
+Argument marshalling only: every function below has the name and the arguments of the C entry
+point it calls (see ``include/wkv.h``); tensors are handed over as raw device pointers and the
+current torch stream as the HIP stream.  Nothing is computed here, and there is no fallback:
+if the HIP library is missing, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwkv.so")
+
+WKV_OK, WKV_ERR_INVALID_ARG, WKV_ERR_UNSUPPORTED, WKV_ERR_WORKSPACE, WKV_ERR_HIP = 0, -1, -2, -3, -4
+WKV_F32, WKV_BF16 = 0, 1
+WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
+WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768
+
+EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
+           "wkv_gather_group", "wkv_compress_groups", "wkv_group_budgets", "wkv_status_string",
+           "wkv_last_error")
+
+
+class WkvError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"wkv status {status}: {message}")
+        self.status = status
+
+
+class _Problem(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("w_obs", C.c_int32), ("max_seq_len", C.c_int32),
+        ("dtype", C.c_int32), ("scale", C.c_float),
+        ("seq_len", C.POINTER(C.c_int32)), ("win", C.POINTER(C.c_int32)),
+        ("top_p", C.POINTER(C.c_int32)), ("k_windows", C.POINTER(C.c_int32)),
+        ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_t", C.c_int64),
+        ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_t", C.c_int64),
+        ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64), ("out_stride_t", C.c_int64),
+    ]
+
+
+class Dims(C.Structure):
+    _fields_ = [("obs_rows", C.c_int32), ("t_stride", C.c_int32), ("nw_max", C.c_int32),
+                ("k_max", C.c_int32), ("nkeep_max", C.c_int32), ("total_tokens", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded HIP library.  Raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_17922_amd.build` "
+                           "(there is no fallback path)")
+    l = C.CDLL(LIB_PATH)
+    P, VP = C.POINTER(_Problem), C.c_void_p
+    l.wkv_get_dims.argtypes = [P, C.POINTER(Dims)]; l.wkv_get_dims.restype = C.c_int
+    l.wkv_workspace_bytes.argtypes = [P, C.c_int32]; l.wkv_workspace_bytes.restype = C.c_size_t
+    l.wkv_score.argtypes = [P, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_score.restype = C.c_int
+    l.wkv_window_pool.argtypes = [P, VP, VP, VP]; l.wkv_window_pool.restype = C.c_int
+    l.wkv_topk_windows.argtypes = [P, VP, VP, VP, VP, VP]; l.wkv_topk_windows.restype = C.c_int
+    l.wkv_gather_group.argtypes = [P, C.c_int32, C.POINTER(VP), C.POINTER(VP), VP, VP,
+                                   C.POINTER(VP), C.POINTER(VP), VP]
+    l.wkv_gather_group.restype = C.c_int
+    l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
+                                      C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP, C.c_size_t, VP]
+    l.wkv_compress_groups.restype = C.c_int
+    l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
+    l.wkv_group_budgets.restype = C.c_int
+    l.wkv_status_string.argtypes = [C.c_int]; l.wkv_status_string.restype = C.c_char_p
+    l.wkv_last_error.argtypes = []; l.wkv_last_error.restype = C.c_char_p
+    _lib = l
+    return l
+
+
+def _check(status: int) -> None:
+    if status != WKV_OK:
+        l = lib()
+        detail = l.wkv_last_error().decode() or l.wkv_status_string(status).decode()
+        raise WkvError(status, detail)
+
+
+def _i32(xs: Sequence[int]):
+    return (C.c_int32 * len(xs))(*[int(x) for x in xs])
+
+
+class Problem:
+    """Host-side description of one batch (mirrors ``wkv_problem``).  Strides are in elements;
+    ``None`` selects contiguous ``[B, H, T, d]`` tensors."""
+
+    def __init__(self, *, n_q_heads: int, n_kv_heads: int, head_dim: int, w_obs: int,
+                 seq_len: Sequence[int], win: Sequence[int], top_p: Sequence[int],
+                 k_windows: Sequence[int], dtype: int, max_seq_len: Optional[int] = None,
+                 scale: float = 0.0, q_strides=None, kv_strides=None, out_strides=None,
+                 nkeep_max: Optional[int] = None):
+        B = len(seq_len)
+        self._keep = [_i32(seq_len), _i32(win), _i32(top_p), _i32(k_windows)]
+        if max_seq_len is None:
+            max_seq_len = max(seq_len) if B else 0
+        if nkeep_max is None:
+            nkeep_max = max([k * w for k, w in zip(k_windows, win)], default=0) + w_obs
+        d = head_dim
+        q_strides = q_strides or (n_q_heads * w_obs * d, w_obs * d, d)
+        kv_strides = kv_strides or (n_kv_heads * max_seq_len * d, max_seq_len * d, d)
+        out_strides = out_strides or (n_kv_heads * nkeep_max * d, nkeep_max * d, d)
+        self.c = _Problem(B, n_q_heads, n_kv_heads, head_dim, w_obs, max_seq_len, dtype, scale,
+                          self._keep[0], self._keep[1], self._keep[2], self._keep[3],
+                          *q_strides, *kv_strides, *out_strides)
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def _ptr(t) -> C.c_void_p:
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _ptr_array(ts):
+    return (C.c_void_p * len(ts))(*[t.data_ptr() if t is not None else 0 for t in ts])
+
+
+def _stream(stream=None) -> C.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def wkv_get_dims(problem: Problem) -> Dims:
+    d = Dims()
+    _check(lib().wkv_get_dims(problem.ref(), C.byref(d)))
+    return d
+
+
+def wkv_workspace_bytes(problem: Problem, n_groups: int = 1) -> int:
+    n = lib().wkv_workspace_bytes(problem.ref(), n_groups)
+    if n == 0:
+        raise WkvError(WKV_ERR_INVALID_ARG, lib().wkv_last_error().decode())
+    return int(n)
+
+
+def wkv_score(problem, q_obs, k_first, t_out, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().wkv_score(problem.ref(), _ptr(q_obs), _ptr(k_first), _ptr(t_out), _ptr(workspace),
+                           ws_bytes, _stream(stream)))
+
+
+def wkv_window_pool(problem, t, s_out, stream=None) -> None:
+    _check(lib().wkv_window_pool(problem.ref(), _ptr(t), _ptr(s_out), _stream(stream)))
+
+
+def wkv_topk_windows(problem, s, win_idx_out, tok_idx_out, n_keep_out, stream=None) -> None:
+    _check(lib().wkv_topk_windows(problem.ref(), _ptr(s), _ptr(win_idx_out), _ptr(tok_idx_out),
+                                  _ptr(n_keep_out), _stream(stream)))
+
+
+def wkv_gather_group(problem, k_layers, v_layers, tok_idx, n_keep, k_out_layers, v_out_layers,
+                     stream=None) -> None:
+    n = len(k_layers)
+    _check(lib().wkv_gather_group(problem.ref(), n, _ptr_array(k_layers), _ptr_array(v_layers), _ptr(tok_idx),
+                                  _ptr(n_keep), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
+                                  _stream(stream)))
+
+
+class CompressCall:
+    """``wkv_compress_groups`` with its host pointer arrays marshalled once, for callers that
+    repeat the same call (the benchmark's timed loop)."""
+
+    def __init__(self, problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers,
+                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace):
+        self._keep = (problem, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
+                      win_idx_out, tok_idx_out, n_keep_out, workspace)
+        ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        self._args = (problem.ref(), n_groups, gamma, _ptr_array(q_obs_groups), _ptr_array(k_layers),
+                      _ptr_array(v_layers), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
+                      _ptr(win_idx_out), _ptr(tok_idx_out), _ptr(n_keep_out), _ptr(workspace), ws_bytes)
+        self._fn = lib().wkv_compress_groups
+
+    def __call__(self, stream=None) -> None:
+        _check(self._fn(*self._args, _stream(stream)))
+
+
+def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers,
+                        v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, stream=None) -> None:
+    CompressCall(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
+                 win_idx_out, tok_idx_out, n_keep_out, workspace)(stream)
+
+
+def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:
+    out = (C.c_double * max(n_groups, 1))()
+    _check(lib().wkv_group_budgets(b_total, n_groups, lam, out))
+    return list(out)[:n_groups]

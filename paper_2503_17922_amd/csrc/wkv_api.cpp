@@ -1,0 +1,166 @@
+// The exported entry points: validate on the host, then enqueue the kernels on the caller's
+// stream.  No allocation, no synchronisation, no state.
+#include <cstring>
+
+#include "wkv_internal.h"
+
+using namespace wkv;
+
+namespace {
+
+inline bool misaligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+wkv_status hip_fail(hipError_t e, const char *what) {
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return WKV_ERR_HIP;
+}
+
+struct Prepared {
+  wkv_dims dims;
+  Shape shape;
+  BatchParams bp;
+};
+
+wkv_status prepare(const wkv_problem *problem, Prepared *out) {
+  wkv_status st = validate(problem, &out->dims);
+  if (st != WKV_OK) return st;
+  fill_shape(problem, out->dims, &out->shape, &out->bp);
+  return WKV_OK;
+}
+
+wkv_status check_workspace(const Shape &s, const ScorePlan &pl, int32_t n_groups, void *ws, size_t bytes,
+                           Workspace *out) {
+  if (!ws) { set_error("workspace is NULL"); return WKV_ERR_WORKSPACE; }
+  if (misaligned(ws, 256)) { set_error("workspace must be 256-byte aligned"); return WKV_ERR_WORKSPACE; }
+  *out = carve_workspace(s, pl, n_groups, ws);
+  if (bytes < out->bytes) {
+    set_error("workspace has %zu bytes, %zu needed", bytes, out->bytes);
+    return WKV_ERR_WORKSPACE;
+  }
+  return WKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *k_first, float *t_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (!q_obs || !k_first || !t_out) { set_error("q_obs / k_first / t_out is NULL"); return WKV_ERR_INVALID_ARG; }
+  if (misaligned(q_obs, 16) || misaligned(k_first, 16)) { set_error("q_obs and k_first must be 16-byte aligned"); return WKV_ERR_INVALID_ARG; }
+  const ScorePlan pl = plan_score(pr.shape, 1);
+  Workspace ws;
+  st = check_workspace(pr.shape, pl, 1, workspace, workspace_bytes, &ws);
+  if (st != WKV_OK) return st;
+  GroupPtrs gp;
+  std::memset(&gp, 0, sizeof(gp));
+  gp.q[0] = q_obs; gp.k[0] = k_first;
+  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, ws.partials, t_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_score launch");
+}
+
+wkv_status wkv_window_pool(const wkv_problem *problem, const float *t, float *s_out, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (!t || !s_out) { set_error("t / s_out is NULL"); return WKV_ERR_INVALID_ARG; }
+  hipError_t e = launch_pool(pr.shape, pr.bp, 1, t, s_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_window_pool launch");
+}
+
+wkv_status wkv_topk_windows(const wkv_problem *problem, const float *s, int32_t *win_idx_out,
+                            int32_t *tok_idx_out, int32_t *n_keep_out, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (!s || !win_idx_out || !tok_idx_out || !n_keep_out) {
+    set_error("s / win_idx_out / tok_idx_out / n_keep_out is NULL"); return WKV_ERR_INVALID_ARG;
+  }
+  hipError_t e = launch_topk(pr.shape, pr.bp, 1, s, win_idx_out, tok_idx_out, n_keep_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_topk_windows launch");
+}
+
+static wkv_status fill_layers(int32_t n_layers, const void *const *k_layers, const void *const *v_layers,
+                              void *const *k_out_layers, void *const *v_out_layers, LayerPtrs *lp) {
+  if (!k_layers || !v_layers || !k_out_layers || !v_out_layers) {
+    set_error("layer pointer arrays must be non-NULL"); return WKV_ERR_INVALID_ARG;
+  }
+  std::memset(lp, 0, sizeof(*lp));
+  for (int32_t l = 0; l < n_layers; ++l) {
+    if (!k_layers[l] || !v_layers[l] || !k_out_layers[l] || !v_out_layers[l]) {
+      set_error("layer %d has a NULL tensor pointer", l); return WKV_ERR_INVALID_ARG;
+    }
+    if (misaligned(k_layers[l], 16) || misaligned(v_layers[l], 16) || misaligned(k_out_layers[l], 16) ||
+        misaligned(v_out_layers[l], 16)) {
+      set_error("layer %d: tensors must be 16-byte aligned", l); return WKV_ERR_INVALID_ARG;
+    }
+    lp->k_in[l] = k_layers[l]; lp->v_in[l] = v_layers[l];
+    lp->k_out[l] = k_out_layers[l]; lp->v_out[l] = v_out_layers[l];
+  }
+  return WKV_OK;
+}
+
+wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers, const void *const *k_layers,
+                            const void *const *v_layers, const int32_t *tok_idx, const int32_t *n_keep,
+                            void *const *k_out_layers, void *const *v_out_layers, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (n_layers < 1 || n_layers > WKV_MAX_LAYERS) { set_error("n_layers outside [1, %d]", WKV_MAX_LAYERS); return WKV_ERR_INVALID_ARG; }
+  if (!tok_idx || !n_keep) { set_error("tok_idx / n_keep is NULL"); return WKV_ERR_INVALID_ARG; }
+  LayerPtrs lp;
+  st = fill_layers(n_layers, k_layers, v_layers, k_out_layers, v_out_layers, &lp);
+  if (st != WKV_OK) return st;
+  // one group: every layer reads the same index rows (gamma = n_layers)
+  hipError_t e = launch_gather(pr.shape, lp, n_layers, n_layers, tok_idx, n_keep, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_gather_group launch");
+}
+
+wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                               const void *const *q_obs_groups, const void *const *k_layers,
+                               const void *const *v_layers, void *const *k_out_layers,
+                               void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
+                               int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (n_groups < 1 || n_groups > WKV_MAX_GROUPS) { set_error("n_groups outside [1, %d]", WKV_MAX_GROUPS); return WKV_ERR_INVALID_ARG; }
+  if (gamma < 1 || (int64_t)n_groups * gamma > WKV_MAX_LAYERS) {
+    set_error("need gamma >= 1 and n_groups*gamma <= %d", WKV_MAX_LAYERS); return WKV_ERR_INVALID_ARG;
+  }
+  if (!q_obs_groups || !win_idx_out || !tok_idx_out || !n_keep_out) {
+    set_error("q_obs_groups / win_idx_out / tok_idx_out / n_keep_out is NULL"); return WKV_ERR_INVALID_ARG;
+  }
+  const int32_t n_layers = n_groups * gamma;
+  LayerPtrs lp;
+  st = fill_layers(n_layers, k_layers, v_layers, k_out_layers, v_out_layers, &lp);
+  if (st != WKV_OK) return st;
+  GroupPtrs gp;
+  std::memset(&gp, 0, sizeof(gp));
+  for (int32_t g = 0; g < n_groups; ++g) {
+    if (!q_obs_groups[g] || misaligned(q_obs_groups[g], 16)) {
+      set_error("q_obs_groups[%d] is NULL or not 16-byte aligned", g); return WKV_ERR_INVALID_ARG;
+    }
+    gp.q[g] = q_obs_groups[g];
+    gp.k[g] = k_layers[(size_t)g * gamma];     // Section 2.2.2: the group's first layer is scored
+  }
+  const ScorePlan pl = plan_score(pr.shape, n_groups);
+  Workspace ws;
+  st = check_workspace(pr.shape, pl, n_groups, workspace, workspace_bytes, &ws);
+  if (st != WKV_OK) return st;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, ws.t, stream);
+  if (e != hipSuccess) return hip_fail(e, "score launch");
+  e = launch_pool(pr.shape, pr.bp, n_groups, ws.t, ws.s, stream);
+  if (e != hipSuccess) return hip_fail(e, "pool launch");
+  e = launch_topk(pr.shape, pr.bp, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
+  if (e != hipSuccess) return hip_fail(e, "top-k launch");
+  e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);
+  if (e != hipSuccess) return hip_fail(e, "gather launch");
+  return WKV_OK;
+}
+
+}  // extern "C"

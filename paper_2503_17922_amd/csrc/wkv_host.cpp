@@ -1,0 +1,207 @@
+// Host-side logic of libwkv: argument validation, derived sizes, launch planning and the
+// scalar helpers.  Nothing in this file touches the GPU, so all of it is testable on a
+// machine without one.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "wkv_internal.h"
+
+namespace wkv {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+wkv_status validate(const wkv_problem *p, wkv_dims *dims) {
+  g_err[0] = 0;
+  if (!p) { set_error("problem is NULL"); return WKV_ERR_INVALID_ARG; }
+  if (!p->seq_len || !p->win || !p->top_p || !p->k_windows) {
+    set_error("seq_len / win / top_p / k_windows must be non-NULL host arrays");
+    return WKV_ERR_INVALID_ARG;
+  }
+  if (p->batch < 1) { set_error("batch must be >= 1 (got %d)", p->batch); return WKV_ERR_INVALID_ARG; }
+  if (p->batch > WKV_MAX_BATCH) {
+    set_error("batch %d exceeds WKV_MAX_BATCH=%d; split the call", p->batch, WKV_MAX_BATCH);
+    return WKV_ERR_UNSUPPORTED;
+  }
+  if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) {
+    set_error("n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
+    return WKV_ERR_INVALID_ARG;
+  }
+  if ((int64_t)p->batch * p->n_kv_heads > 65535) {
+    set_error("batch * n_kv_heads exceeds 65535 (launch grid limit); split the call"); return WKV_ERR_UNSUPPORTED;
+  }
+  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16) {
+    set_error("unknown dtype %d", p->dtype); return WKV_ERR_INVALID_ARG;
+  }
+  if (p->head_dim != 64 && p->head_dim != 128) {
+    set_error("head_dim %d is not supported (64 or 128)", p->head_dim); return WKV_ERR_UNSUPPORTED;
+  }
+  if (p->w_obs < 1) { set_error("w_obs must be >= 1"); return WKV_ERR_INVALID_ARG; }
+  const int64_t G = p->n_q_heads / p->n_kv_heads;
+  if (G * p->w_obs > WKV_MAX_OBS_ROWS) {
+    set_error("(Hq/Hkv)*w_obs = %lld exceeds WKV_MAX_OBS_ROWS=%d", (long long)(G * p->w_obs), WKV_MAX_OBS_ROWS);
+    return WKV_ERR_UNSUPPORTED;
+  }
+  if (p->max_seq_len < p->w_obs) { set_error("max_seq_len < w_obs"); return WKV_ERR_INVALID_ARG; }
+  if (!(p->scale >= 0.0f) || std::isinf(p->scale)) {
+    set_error("scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))"); return WKV_ERR_INVALID_ARG;
+  }
+  const int64_t d = p->head_dim;
+  if (p->q_stride_t < d || p->kv_stride_t < d || p->out_stride_t < d) {
+    set_error("token strides must be >= head_dim"); return WKV_ERR_INVALID_ARG;
+  }
+  // 16-byte vector loads: every row start must be 16-byte aligned relative to the base.
+  const int64_t vec = p->dtype == WKV_BF16 ? 8 : 4;
+  const int64_t strides[9] = {p->q_stride_b, p->q_stride_h, p->q_stride_t, p->kv_stride_b, p->kv_stride_h,
+                              p->kv_stride_t, p->out_stride_b, p->out_stride_h, p->out_stride_t};
+  for (int i = 0; i < 9; ++i) {
+    if (strides[i] < 0 || strides[i] % vec != 0) {
+      set_error("strides must be non-negative multiples of %lld elements (16 bytes)", (long long)vec);
+      return WKV_ERR_INVALID_ARG;
+    }
+  }
+  if (p->kv_stride_h < d || p->q_stride_h < d || p->out_stride_h < d) {
+    set_error("head strides must be >= head_dim"); return WKV_ERR_INVALID_ARG;
+  }
+
+  wkv_dims dm;
+  std::memset(&dm, 0, sizeof(dm));
+  dm.obs_rows = (int32_t)(G * p->w_obs);
+  dm.t_stride = p->max_seq_len - p->w_obs;
+  for (int b = 0; b < p->batch; ++b) {
+    const int64_t L = p->seq_len[b], w = p->win[b], tp = p->top_p[b], k = p->k_windows[b];
+    if (L < p->w_obs || L > p->max_seq_len) {
+      set_error("seq_len[%d]=%lld outside [w_obs=%d, max_seq_len=%d]", b, (long long)L, p->w_obs, p->max_seq_len);
+      return WKV_ERR_INVALID_ARG;
+    }
+    if (w < 1) { set_error("win[%d] must be >= 1", b); return WKV_ERR_INVALID_ARG; }
+    if (w > WKV_MAX_WIN) { set_error("win[%d]=%lld exceeds WKV_MAX_WIN=%d", b, (long long)w, WKV_MAX_WIN); return WKV_ERR_UNSUPPORTED; }
+    if (tp < 1) { set_error("top_p[%d] must be >= 1", b); return WKV_ERR_INVALID_ARG; }
+    const int64_t nw = ceil_div(L - p->w_obs, w);
+    if (nw > WKV_MAX_WINDOWS) { set_error("sequence %d has %lld windows (> WKV_MAX_WINDOWS=%d)", b, (long long)nw, WKV_MAX_WINDOWS); return WKV_ERR_UNSUPPORTED; }
+    if (k < 0 || k > nw) { set_error("k_windows[%d]=%lld outside [0, NW=%lld]", b, (long long)k, (long long)nw); return WKV_ERR_INVALID_ARG; }
+    if (nw > dm.nw_max) dm.nw_max = (int32_t)nw;
+    if (k > dm.k_max) dm.k_max = (int32_t)k;
+    if (k * w + p->w_obs > dm.nkeep_max) dm.nkeep_max = (int32_t)(k * w + p->w_obs);
+    dm.total_tokens += L;
+  }
+  if (dims) *dims = dm;
+  return WKV_OK;
+}
+
+void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParams *bp) {
+  s->B = p->batch; s->Hq = p->n_q_heads; s->Hkv = p->n_kv_heads; s->d = p->head_dim;
+  s->w_obs = p->w_obs; s->G = p->n_q_heads / p->n_kv_heads; s->M = dims.obs_rows;
+  s->t_stride = dims.t_stride; s->nw_max = dims.nw_max; s->k_max = dims.k_max;
+  s->nkeep_max = dims.nkeep_max; s->dtype = p->dtype;
+  const double scale = p->scale > 0.0f ? (double)p->scale : 1.0 / std::sqrt((double)p->head_dim);
+  s->c1 = (float)(scale * 1.4426950408889634074);
+  s->q_sb = p->q_stride_b; s->q_sh = p->q_stride_h; s->q_st = p->q_stride_t;
+  s->kv_sb = p->kv_stride_b; s->kv_sh = p->kv_stride_h; s->kv_st = p->kv_stride_t;
+  s->o_sb = p->out_stride_b; s->o_sh = p->out_stride_h; s->o_st = p->out_stride_t;
+  std::memset(bp, 0, sizeof(*bp));
+  for (int b = 0; b < p->batch; ++b) {
+    bp->seq[b].L = p->seq_len[b];
+    bp->seq[b].win = p->win[b];
+    bp->seq[b].p = p->top_p[b] < p->win[b] ? p->top_p[b] : p->win[b];
+    bp->seq[b].k = p->k_windows[b];
+  }
+}
+
+static int32_t pick_chunk(int64_t keys_per_problem, int64_t problems, int32_t lo, int32_t hi) {
+  // Aim for about 2048 workgroups over the whole launch (256 CUs, several resident each),
+  // with power-of-two chunks between lo and hi keys.
+  int64_t total = keys_per_problem * problems;
+  int32_t c = hi;
+  while (c > lo && total / c < 2048) c >>= 1;
+  return c;
+}
+
+ScorePlan plan_score(const Shape &s, int32_t n_groups) {
+  ScorePlan pl;
+  pl.m_pad = (s.M + 15) / 16 * 16;
+  pl.mfma = (s.dtype == WKV_BF16) && pl.m_pad <= 128;
+  const int64_t problems = (int64_t)s.B * s.Hkv * n_groups;
+  const int32_t Lmax = s.t_stride + s.w_obs;
+  pl.chunk1 = pick_chunk(Lmax, problems, 256, 2048);
+  pl.n_chunks1 = (int32_t)ceil_div(Lmax, pl.chunk1);
+  pl.chunk2 = pick_chunk(s.t_stride > 0 ? s.t_stride : 1, problems, 256, 2048);
+  pl.n_chunks2 = (int32_t)ceil_div(s.t_stride > 0 ? s.t_stride : 1, pl.chunk2);
+  return pl;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base) {
+  Workspace w;
+  const size_t rows = (size_t)n_groups * s.B * s.Hkv;
+  const size_t part = align256(rows * plan.m_pad * plan.n_chunks1 * sizeof(float2));
+  const size_t tb = align256(rows * (size_t)(s.t_stride > 0 ? s.t_stride : 1) * sizeof(float));
+  const size_t sb = align256(rows * (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(float));
+  char *b = (char *)base;
+  w.partials = (float2 *)b;
+  w.t = (float *)(b + part);
+  w.s = (float *)(b + part + tb);
+  w.bytes = part + tb + sb;
+  return w;
+}
+
+}  // namespace wkv
+
+using namespace wkv;
+
+extern "C" {
+
+wkv_status wkv_get_dims(const wkv_problem *problem, wkv_dims *dims) {
+  if (!dims) { set_error("dims is NULL"); return WKV_ERR_INVALID_ARG; }
+  return validate(problem, dims);
+}
+
+size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups) {
+  wkv_dims dm;
+  if (validate(problem, &dm) != WKV_OK) return 0;
+  if (n_groups < 1 || n_groups > WKV_MAX_GROUPS) { set_error("n_groups outside [1, %d]", WKV_MAX_GROUPS); return 0; }
+  Shape s; BatchParams bp;
+  fill_shape(problem, dm, &s, &bp);
+  ScorePlan pl = plan_score(s, n_groups);
+  return carve_workspace(s, pl, n_groups, nullptr).bytes;
+}
+
+wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda, double *budgets_out) {
+  if (!budgets_out) { set_error("budgets_out is NULL"); return WKV_ERR_INVALID_ARG; }
+  if (n_groups < 1 || !(lambda > 0.0) || !(b_total >= 0.0)) {
+    set_error("need n_groups >= 1, lambda > 0, b_total >= 0"); return WKV_ERR_INVALID_ARG;
+  }
+  const double H = (double)n_groups;
+  if (n_groups == 1) { budgets_out[0] = b_total; return WKV_OK; }
+  const double top = b_total / (lambda * H);          // Eq. 6, group H-1
+  const double bottom = 2.0 * b_total / H - top;      // Eq. 6, group 0
+  const double step = (bottom - top) / (H - 1.0);     // Eq. 7
+  for (int32_t h = 0; h < n_groups; ++h) budgets_out[h] = bottom - step * (double)h;
+  return WKV_OK;
+}
+
+const char *wkv_status_string(wkv_status st) {
+  switch (st) {
+    case WKV_OK: return "ok";
+    case WKV_ERR_INVALID_ARG: return "invalid argument";
+    case WKV_ERR_UNSUPPORTED: return "unsupported problem";
+    case WKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case WKV_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+const char *wkv_last_error(void) { return g_err; }
+
+}  // extern "C"

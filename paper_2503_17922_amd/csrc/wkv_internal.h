@@ -1,0 +1,83 @@
+// Internal declarations shared by the translation units of libwkv (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wkv.h"
+
+namespace wkv {
+
+// Per-sequence parameters, passed to kernels by value inside the kernel argument block so
+// that no host-to-device copy (and no allocation) is ever needed for metadata.
+struct SeqParam {
+  int32_t L;    // prefix length
+  int32_t win;  // review-window size (omega)
+  int32_t p;    // top-p, already clamped to [1, win]
+  int32_t k;    // windows to keep
+};
+struct BatchParams {
+  SeqParam seq[WKV_MAX_BATCH];
+};
+
+// Per-group device pointers of the scored layer.
+struct GroupPtrs {
+  const void *q[WKV_MAX_GROUPS];
+  const void *k[WKV_MAX_GROUPS];
+};
+
+// Per-layer device pointers for the gather.
+struct LayerPtrs {
+  const void *k_in[WKV_MAX_LAYERS];
+  const void *v_in[WKV_MAX_LAYERS];
+  void *k_out[WKV_MAX_LAYERS];
+  void *v_out[WKV_MAX_LAYERS];
+};
+
+// Problem shape as the kernels see it.
+struct Shape {
+  int32_t B, Hq, Hkv, d, w_obs, G;
+  int32_t M;          // G * w_obs softmax rows per KV head
+  int32_t t_stride, nw_max, k_max, nkeep_max;
+  int32_t dtype;
+  float c1;           // logit scale * log2(e): logits are handled in base-2 units
+  int64_t q_sb, q_sh, q_st;
+  int64_t kv_sb, kv_sh, kv_st;
+  int64_t o_sb, o_sh, o_st;
+};
+
+// How the score passes split the key axis into workgroup chunks.
+struct ScorePlan {
+  int32_t chunk1, n_chunks1;   // stats pass
+  int32_t chunk2, n_chunks2;   // score pass (over t_stride)
+  int32_t m_pad;               // rows padded to a multiple of 16
+  bool mfma;                   // bf16 MFMA kernels (else the generic ones)
+};
+
+struct Workspace {
+  float2 *partials;   // [n_groups][B][Hkv][m_pad][n_chunks1] (running max, sum) in base 2
+  float *t;           // [n_groups][B][Hkv][t_stride]
+  float *s;           // [n_groups][B][Hkv][nw_max]
+  size_t bytes;
+};
+
+// ---- host-side helpers (wkv_host.cpp) ---------------------------------------------------
+void set_error(const char *fmt, ...);
+wkv_status validate(const wkv_problem *p, wkv_dims *dims);
+void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParams *bp);
+ScorePlan plan_score(const Shape &s, int32_t n_groups);
+Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base);
+
+// ---- launchers (one per kernel family) ----------------------------------------------------
+// All return hipSuccess or the launch error. Pointers are device pointers unless noted.
+hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &plan,
+                        const GroupPtrs &gp, int32_t n_groups, float2 *partials, float *t_out,
+                        hipStream_t stream);
+hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
+                       float *s_out, hipStream_t stream);
+hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
+                       int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream);
+hipError_t launch_gather(const Shape &s, const LayerPtrs &lp, int32_t n_layers, int32_t gamma,
+                         const int32_t *tok_idx, const int32_t *n_keep, hipStream_t stream);
+
+}  // namespace wkv

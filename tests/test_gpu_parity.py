@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded
+inputs — the five named configurations at full size plus edge cases."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_17922_amd as W
+import wkv_synth as S
+from oracle import wkv_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample(items, n, seed):
+    items = list(items)
+    if n is None or n >= len(items):
+        return items
+    rng = np.random.default_rng(seed)
+    pick = rng.choice(len(items), size=n, replace=False)
+    return [items[i] for i in sorted(pick)]
+
+
+def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check_stage_group=0):
+    """One wkv_compress_groups call checked against the oracle.
+
+    n_oracle: how many (group, b, h) problems the oracle recomputes (None = all).
+    n_gather_cpu: how many (layer, K|V, b, h) slices are compared on the CPU with the oracle's
+    gather (None = all); every slice is additionally compared on the device.
+    """
+    st = P.DeviceState(w, device)
+    print(f"[{w.name}] L={w.seq_len} win={w.win} p={w.top_p} k={w.k_windows} groups={w.n_groups}x{w.gamma} "
+          f"ws={st.ws_bytes >> 10} KiB", flush=True)
+    P.check_generator_matches(w, S.KIND_K, 0, st.k[0], 0, 0)
+    P.check_generator_matches(w, S.KIND_V, w.n_layers - 1, st.v[-1], w.batch - 1, w.n_kv_heads - 1)
+    k_before = st.k[0][0, 0, : min(64, w.seq_len[0])].clone()
+    st.compress()
+    assert torch.equal(k_before, st.k[0][0, 0, : min(64, w.seq_len[0])]), "inputs were modified"
+
+    win_idx = st.win_idx.cpu().numpy()[..., : st.dims.k_max]          # (allocated with >= 1 column)
+    tok_idx = st.tok_idx.cpu().numpy(); n_keep = st.n_keep.cpu().numpy()
+    B, H = w.batch, w.n_kv_heads
+
+    # ---- stage calls reproduce the batched call bit for bit, and expose t and s ----------------
+    g0 = check_stage_group
+    t_dev, s_dev, wi, ti, nk = st.stages(g0)
+    assert np.array_equal(wi.cpu().numpy()[..., : st.dims.k_max], win_idx[g0]) and np.array_equal(ti.cpu().numpy(), tok_idx[g0])
+    assert np.array_equal(nk.cpu().numpy(), n_keep[g0])
+    t_host = t_dev.cpu().numpy().astype(np.float64); s_host = s_dev.cpu().numpy().astype(np.float64)
+
+    # ---- structure of every index row -------------------------------------------------------------
+    sels = {}
+    for g, b, h in itertools.product(range(w.n_groups), range(B), range(H)):
+        sels[g, b, h] = P.check_indices_structure(w, b, win_idx[g, b, h], tok_idx[g, b, h], int(n_keep[g, b, h]),
+                                                  st.dims.k_max, st.dims.nkeep_max, f"{w.name} g{g} b{b} h{h}")
+
+    # ---- oracle on (sampled) problems ----------------------------------------------------------------
+    problems = _sample(itertools.product(range(w.n_groups), range(B), range(H)), n_oracle, 1)
+    if (g0, 0, 0) not in problems:
+        problems.append((g0, 0, 0))
+    exact = 0
+    for g, b, h in problems:
+        t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
+        what = f"{w.name} g{g} b{b} h{h}"
+        if g == g0:
+            n_rev = w.seq_len[b] - w.w_obs
+            P.assert_scores_close(t_host[b, h, :n_rev], t, what + " t")
+            assert np.all(t_host[b, h, n_rev:] == 0.0), what + " t padding"
+            P.assert_scores_close(s_host[b, h, : len(s)], s, what + " s")
+            assert np.all(np.isneginf(s_host[b, h, len(s):])), what + " s padding"
+        same = P.check_selection(s, sel, sels[g, b, h], w.k_windows[b], what)
+        exact += same
+        if same:
+            assert np.array_equal(tok_idx[g, b, h, : len(idx)], idx), what + " tok_idx"
+    print(f"[{w.name}] oracle problems: {len(problems)}, identical selections: {exact}", flush=True)
+
+    # ---- gather: every layer, bit exact ----------------------------------------------------------------
+    slices = list(itertools.product(range(w.n_layers), (S.KIND_K, S.KIND_V), range(B), range(H)))
+    for l, kind, b, h in _sample(slices, n_gather_cpu, 2):
+        g = l // w.gamma
+        src = (st.k if kind == S.KIND_K else st.v)[l]
+        out = (st.k_out if kind == S.KIND_K else st.v_out)[l]
+        n = int(n_keep[g, b, h])
+        rows = src[b, h, : w.seq_len[b]].cpu()
+        rows = rows.numpy() if w.dtype == "f32" else rows.view(torch.int16).numpy()
+        got = out[b, h].cpu()
+        got = got.numpy() if w.dtype == "f32" else got.view(torch.int16).numpy()
+        want = O.gather_rows(rows, tok_idx[g, b, h, :n])
+        assert np.array_equal(got[:n], want), f"{w.name} gather layer {l} kind {kind} b{b} h{h}"
+        assert not got[n:].any(), f"{w.name} gather zero padding layer {l} b{b} h{h}"
+    for l in range(w.n_layers):          # all slices, compared in device memory
+        g = l // w.gamma
+        for b in range(B):
+            idx_dev = st.tok_idx[g, b].to(torch.int64)
+            for src, out in ((st.k[l], st.k_out[l]), (st.v[l], st.v_out[l])):
+                for h in range(H):
+                    n = int(n_keep[g, b, h])
+                    assert torch.equal(out[b, h, :n], src[b, h].index_select(0, idx_dev[h, :n]))
+                    assert not out[b, h, n:].any()
+    return st, sels
+
+
+# ---------------------------------------------------------------------------------------
+# the named configurations, full size
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["c1", "c2", "c3a", "c3b"])
+def test_config_small(name, device):
+    run_and_check(S.make_workload(name), device)
+
+
+def test_config_c4_full_model(device):
+    w = S.make_workload("c4")
+    st, sels = run_and_check(w, device, n_oracle=24, n_gather_cpu=12, check_stage_group=3)
+    # every window inside a planted span is kept, in every KV head of every scoring layer
+    for (g, b, h), sel in sels.items():
+        kept = set(int(x) for x in sel)
+        for s0 in w.span_starts()[b]:
+            want = set(range(s0 // w.win[b], (s0 + w.span_len) // w.win[b]))
+            assert want <= kept, f"planted span at {s0} not kept in g{g} h{h}"
+
+
+def test_config_c5_batched_mixed(device):
+    w = S.make_workload("c5")
+    run_and_check(w, device, n_oracle=32, n_gather_cpu=16, check_stage_group=5)
+
+
+# ---------------------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------------------
+def _mini(**kw):
+    base = dict(name="mini", seed=77, dtype="bf16", n_groups=2, gamma=2, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                w_obs=16, seq_len=[700], win=[8], top_p=[8], k_windows=[10])
+    base.update(kw)
+    return S.Workload(**base)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                                               # ragged: 684 review tokens, tail of 4
+    dict(seq_len=[700], win=[8], k_windows=[86]),                         # keep every window incl. the partial one
+    dict(seq_len=[700], k_windows=[0]),                                   # keep only the observation window
+    dict(seq_len=[16], k_windows=[0]),                                    # no review context at all
+    dict(seq_len=[17], win=[8], k_windows=[1]),                           # one review token
+    dict(seq_len=[1000, 16, 333, 2048], win=[8, 8, 32, 128], top_p=[4, 8, 1, 64], k_windows=[20, 0, 3, 5]),
+    dict(win=[1], top_p=[1], k_windows=[100]),                            # token-level selection
+    dict(win=[128], top_p=[128], k_windows=[2]),
+    dict(win=[24], top_p=[7], k_windows=[9]),                             # window size not a power of two
+    dict(n_q_heads=6, n_kv_heads=2, w_obs=5),                             # 15 softmax rows
+    dict(n_q_heads=12, n_kv_heads=2, w_obs=4, seq_len=[5000], k_windows=[30]),    # Qwen-like G=6, alpha=4
+    dict(n_q_heads=4, n_kv_heads=4, w_obs=1),                             # a single observation query per head
+    dict(head_dim=64, seq_len=[3000], k_windows=[40]),
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[1500]),           # 256 rows: generic kernels, bf16
+    dict(dtype="f32", head_dim=128, seq_len=[900]),
+    dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=1, w_obs=64, seq_len=[600]),
+    dict(n_groups=1, gamma=1, seq_len=[4097], win=[16], top_p=[8], k_windows=[31]),
+])
+def test_edge_cases(kw, device):
+    run_and_check(_mini(**kw), device)
+
+
+def test_large_logits_are_stable(device):
+    # keys scaled so that logits reach hundreds: exponentials must never overflow
+    w = _mini(seq_len=[2000], k_windows=[12], n_groups=1, gamma=1)
+    st = P.DeviceState(w, device)
+    st.k[0].mul_(24.0)
+    st.compress()
+    t_dev, s_dev, *_ = st.stages(0)
+    assert torch.isfinite(t_dev).all()
+    for h in range(w.n_kv_heads):
+        t, s, sel, idx = P.oracle_problem(w, st.q[0], st.k[0], 0, h)
+        got = t_dev[0, h, : len(t)].cpu().numpy().astype(np.float64)
+        big = t > 1e-6 * t.max()
+        P.assert_scores_close(got[big], t[big], f"large logits h{h}")
+        assert np.all(got[~big] <= 2e-6 * t.max())
+        P.check_selection(s, sel, st.win_idx[0, 0, h, : w.k_windows[0]].cpu().numpy(), w.k_windows[0], f"h{h}")
+
+
+def test_strided_layout(device):
+    # K/V stored [B, L, Hkv, d] (token-major), q [B, w_obs, Hq, d], compact cache [B, n, Hkv, d]
+    w = _mini(seq_len=[1234, 600], win=[8, 8], top_p=[8, 3], k_windows=[17, 9], n_groups=1, gamma=2)
+    st = P.DeviceState(w, device)
+    st.compress()
+    B, H, Lm, d, Hq, a = w.batch, w.n_kv_heads, w.max_seq_len, w.head_dim, w.n_q_heads, w.w_obs
+    nk = st.dims.nkeep_max
+    prob = P.make_problem(w, q_strides=(a * Hq * d, d, Hq * d), kv_strides=(Lm * H * d, d, H * d),
+                          out_strides=(nk * H * d, d, H * d))
+    q2 = [q.permute(0, 2, 1, 3).contiguous() for q in st.q]
+    k2 = [k.permute(0, 2, 1, 3).contiguous() for k in st.k]
+    v2 = [v.permute(0, 2, 1, 3).contiguous() for v in st.v]
+    ko = [torch.full((B, nk, H, d), 5.0, dtype=k.dtype, device=device) for k in st.k]
+    vo = [torch.full((B, nk, H, d), 5.0, dtype=k.dtype, device=device) for k in st.k]
+    wi, ti, nkp = torch.empty_like(st.win_idx), torch.empty_like(st.tok_idx), torch.empty_like(st.n_keep)
+    W.wkv_compress_groups(prob, 1, 2, q2, k2, v2, ko, vo, wi, ti, nkp, st.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(wi, st.win_idx) and torch.equal(ti, st.tok_idx) and torch.equal(nkp, st.n_keep)
+    for l in range(2):
+        assert torch.equal(ko[l].permute(0, 2, 1, 3), st.k_out[l]) and torch.equal(vo[l].permute(0, 2, 1, 3), st.v_out[l])
+
+
+def test_other_layers_do_not_influence_indices(device):
+    w = _mini(seq_len=[900], n_groups=1, gamma=3)
+    st = P.DeviceState(w, device)
+    st.compress()
+    first = st.tok_idx.clone()
+    st.k[1].normal_(); st.k[2].normal_(); st.v[0].normal_()
+    st.compress()
+    assert torch.equal(first, st.tok_idx)
+
+
+def test_topk_ties_and_arbitrary_scores(device):
+    # wkv_topk_windows alone on hand-made score rows: duplicates, negatives, zeros, -inf padding
+    rng = np.random.default_rng(5)
+    L, a, win = 8 * 300 + 16, 16, 8
+    for k in (0, 1, 7, 150, 300):
+        prob = W.Problem(n_q_heads=4, n_kv_heads=4, head_dim=64, w_obs=a, seq_len=[L], win=[win], top_p=[win],
+                         k_windows=[k], dtype=W.WKV_BF16)
+        s = np.stack([rng.integers(0, 12, 300).astype(np.float32) / 4 - 1,          # many exact ties
+                      rng.standard_normal(300).astype(np.float32),
+                      np.zeros(300, np.float32),
+                      np.where(rng.random(300) < 0.5, np.float32(0.25), np.float32(-np.inf))])
+        s_dev = torch.from_numpy(s).to(device)[None]
+        wi = torch.empty((1, 4, max(k, 1)), dtype=torch.int32, device=device)
+        ti = torch.empty((1, 4, k * win + a), dtype=torch.int32, device=device)
+        nk = torch.empty((1, 4), dtype=torch.int32, device=device)
+        W.wkv_topk_windows(prob, s_dev, wi, ti, nk)
+        torch.cuda.synchronize()
+        for h in range(4):
+            want = O.select_windows(s[h].astype(np.float64), k)
+            assert np.array_equal(wi[0, h, :k].cpu().numpy(), want), (k, h)
+            assert np.array_equal(ti[0, h].cpu().numpy(), O.token_indices(want, win, L, a))
+            assert int(nk[0, h]) == k * win + a
+
+
+def test_window_pool_alone(device):
+    rng = np.random.default_rng(6)
+    a = 16
+    for win, p, L in ((8, 8, 1000), (8, 3, 1001), (32, 16, 5000), (128, 17, 4000), (5, 2, 333), (1, 1, 100)):
+        prob = W.Problem(n_q_heads=2, n_kv_heads=2, head_dim=64, w_obs=a, seq_len=[L], win=[win], top_p=[p],
+                         k_windows=[0], dtype=W.WKV_BF16)
+        t = rng.random((1, 2, L - a)).astype(np.float32)
+        t[0, 1, ::3] = t[0, 1, 1::3][: len(t[0, 1, ::3])]      # repeated values inside windows
+        nw = -(-(L - a) // win)
+        s_dev = torch.empty((1, 2, nw), dtype=torch.float32, device=device)
+        W.wkv_window_pool(prob, torch.from_numpy(t).to(device), s_dev)
+        torch.cuda.synchronize()
+        for h in range(2):
+            want = O.window_scores(t[0, h].astype(np.float64), win, p)
+            np.testing.assert_allclose(s_dev[0, h].cpu().numpy(), want, rtol=2e-6)
