@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the WindowKV window-selection path on one MI355X.
+
+One *step* is one ``wkv_compress_groups`` call over the whole workload: score the first layer
+of every group, pool, select, and gather the kept K/V rows of every layer.  The default
+workload is the 32K-token full-model configuration (8 groups of 4 LLaMA-3-8B shaped layers).
+Inputs are seeded synthetic tensors, resident in HBM before the timed region starts.
+
+Prints one JSON line:
+  value      prefix tokens compressed per second per layer group = L * n_groups / step time
+  roofline   the kernel that takes the largest share of the step, its algorithmic HBM bytes per
+             launch over its mean duration (HIP events on the launch stream, measured here)
+  pipeline   the same for the whole step (all kernels, launch gaps included)
+  cpu_baseline  the fp64 CPU oracle timed on this host on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), scaled by the
+# same counters' reading for a plain copy of known size; see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(w):
+    """Bytes each kernel must move per launch (what the method needs, not what a kernel happens
+    to read).  For the whole path the key stream of the scored layers is charged ONCE, although
+    the two score kernels each read it: the second read is this implementation's cost."""
+    e = 2 if w.dtype == "bf16" else 4
+    d, H = w.head_dim, w.n_kv_heads
+    row = d * e
+    k_first = sum(w.seq_len) * H * row * w.n_groups                      # K of each scored layer, once
+    q = w.batch * w.n_q_heads * w.w_obs * row * w.n_groups
+    n_keep = sum(k * wn + w.w_obs for k, wn in zip(w.k_windows, w.win))    # rows kept per KV head
+    gather_rw = w.n_layers * 2 * n_keep * H * row                       # read, and the same written
+    t_bytes = sum(L - w.w_obs for L in w.seq_len) * H * 4 * w.n_groups
+    return {
+        "score_stats": k_first + q,          # one full read of the scored keys
+        "score": k_first + q + t_bytes,      # the second read is algorithmic for this kernel alone
+        "window_pool": t_bytes,
+        "topk_windows": t_bytes // max(min(w.win), 1),
+        "gather": 2 * gather_rw,
+        "pipeline": k_first + q + 2 * gather_rw,    # the path: keys once + gather read + write
+    }
+
+
+def score_flops(w):
+    return 2 * w.n_q_heads * w.w_obs * w.head_dim * sum(w.seq_len) * w.n_groups
+
+
+def cpu_baseline(w, st, budget_s=12.0):
+    """Time the oracle, as it stands, on whole layer groups of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import wkv_oracle as O
+    from tests import parity as P
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    done_groups, t_total = 0, 0.0
+    for g in range(w.n_groups):
+        # stage the group's inputs on the host first: the transfer is not part of the baseline
+        G = w.q_per_kv
+        q = [[P.host_f64(w, st.q[g][b, h * G:(h + 1) * G]) for h in range(w.n_kv_heads)] for b in range(w.batch)]
+        ks = [[[st.k[g * w.gamma + l][b, h, : w.seq_len[b]].cpu() for l in range(w.gamma)]
+               for h in range(w.n_kv_heads)] for b in range(w.batch)]
+        vs = [[[st.v[g * w.gamma + l][b, h, : w.seq_len[b]].cpu() for l in range(w.gamma)]
+               for h in range(w.n_kv_heads)] for b in range(w.batch)]
+        t0 = time.perf_counter()
+        for b in range(w.batch):
+            for h in range(w.n_kv_heads):
+                k64 = ks[b][h][0].to(torch.float64).numpy()
+                _, _, _, idx = O.select_indices(q[b][h], k64, w.win[b], w.top_p[b], w.k_windows[b])
+                for l in range(w.gamma):
+                    O.gather_rows(ks[b][h][l].view(torch.int16).numpy() if w.dtype == "bf16" else ks[b][h][l].numpy(), idx)
+                    O.gather_rows(vs[b][h][l].view(torch.int16).numpy() if w.dtype == "bf16" else vs[b][h][l].numpy(), idx)
+        t_total += time.perf_counter() - t0
+        done_groups += 1
+        if t_total >= budget_s:
+            break
+    per_group = t_total / done_groups
+    return {"value": sum(w.seq_len) / per_group, "unit": "prefix tokens/s per layer group", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"{done_groups} of {w.n_groups} layer groups of workload {w.name} "
+                      f"({done_groups * w.batch * w.n_kv_heads} (sequence, KV head) problems, fp64 numpy, "
+                      f"{t_total:.1f} s; inputs already on the host)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2503_17922_amd as W
+    import wkv_synth as S
+    from tests import parity as P
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    W.lib()
+    device = torch.device("cuda:0")
+    w = S.make_workload(args.workload)
+    st = P.DeviceState(w, device)
+    call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, st.k, st.v, st.k_out, st.v_out,
+                          st.win_idx, st.tok_idx, st.n_keep, st.workspace)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    for _ in range(args.warmup):
+        call(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call(stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    stage_ms = [0.0] * W.WKV_N_STAGES
+    n_prof = max(5, min(args.steps, 20))
+    for _ in range(n_prof):
+        ms = call.profiled(stream)
+        stage_ms = [a + b for a, b in zip(stage_ms, ms)]
+    stage_ms = [a / n_prof for a in stage_ms]
+    stages = dict(zip(W.STAGE_NAMES, stage_ms))
+
+    ab = algorithmic_bytes(w)
+    dominant = max(stages, key=stages.get)
+    ach = ab[dominant] / (stages[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)),
+                "algorithmic_bytes": ab[dominant], "ms": round(stages[dominant], 4)}
+    pipe_ach = ab["pipeline"] / (ms_per_step * 1e-3) / 1e9
+    kernels = {}
+    for name in W.STAGE_NAMES:
+        if stages[name] > 0:
+            kernels[name] = {"ms": round(stages[name], 4), "algorithmic_bytes": ab[name],
+                             "GB/s": round(ab[name] / (stages[name] * 1e-3) / 1e9, 1)}
+    for name in ("score_stats", "score"):
+        if stages[name] > 0:
+            tf = score_flops(w) / (stages[name] * 1e-3) / 1e12
+            kernels[name]["mfma_TFLOP/s"] = round(tf, 1)
+            kernels[name]["mfma_frac"] = round(tf / MFMA_BF16_PEAK_TFLOPS, 4)
+
+    tokens = sum(w.seq_len)
+    out = {
+        "metric": "prefix tokens compressed/sec per layer group; achieved HBM GB/s vs peak",
+        "value": tokens * w.n_groups / (ms_per_step * 1e-3),
+        "unit": "prefix tokens/s per layer group",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_groups} groups x {w.gamma} layers, "
+                               f"{w.n_q_heads}q/{w.n_kv_heads}kv heads, d={w.head_dim}, L={w.seq_len}, "
+                               f"w_obs={w.w_obs}, win={sorted(set(w.win))}, top_p={sorted(set(w.top_p))}, "
+                               f"k={w.k_windows}",
+                   "ms_per_group": ms_per_step / w.n_groups},
+        "roofline": roofline,
+        "pipeline": {"bound": "hbm", "algorithmic_bytes": ab["pipeline"], "achieved": round(pipe_ach, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pipe_ach / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "pipeline"))},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, st)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -175,6 +175,24 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Diagnostic twin of wkv_compress_groups (same arguments, same results, same launches): it
+ * brackets every kernel of the path with HIP events on the caller's stream, waits for the
+ * stream, and reports each kernel's duration.  It creates and destroys HIP events and blocks
+ * the calling thread, so it is for benchmarks and profiling, not for serving.
+ *   stage_ms_out  host float [WKV_N_STAGES]: milliseconds of, in order, the softmax-statistics
+ *                 pass (Eq. 1), the score pass (Eq. 1-2), window pooling (Eq. 3-4), top-k
+ *                 selection (2.2.1) and the shared-index gather (2.2.2).
+ */
+#define WKV_N_STAGES 5
+wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                                        const void *const *q_obs_groups,
+                                        const void *const *k_layers, const void *const *v_layers,
+                                        void *const *k_out_layers, void *const *v_out_layers,
+                                        int32_t *win_idx_out, int32_t *tok_idx_out,
+                                        int32_t *n_keep_out, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream, float *stage_ms_out);
+
+/*
  * Section 2.2.3, Eq. 5-7 (host only): arithmetic-sequence budgets for n_groups groups,
  * b^{H-1} = b_total/(lambda*H), b^0 = 2*b_total/H - b^{H-1}, linear in between.
  *   budgets_out  host double [n_groups], real-valued as in the paper; turning a budget into

@@ -18,9 +18,11 @@ WKV_OK, WKV_ERR_INVALID_ARG, WKV_ERR_UNSUPPORTED, WKV_ERR_WORKSPACE, WKV_ERR_HIP
 WKV_F32, WKV_BF16 = 0, 1
 WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
 WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768
+WKV_N_STAGES = 5
+STAGE_NAMES = ("score_stats", "score", "window_pool", "topk_windows", "gather")
 
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
-           "wkv_gather_group", "wkv_compress_groups", "wkv_group_budgets", "wkv_status_string",
+           "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string",
            "wkv_last_error")
 
 
@@ -72,6 +74,8 @@ def lib() -> C.CDLL:
     l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
                                       C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP, C.c_size_t, VP]
     l.wkv_compress_groups.restype = C.c_int
+    l.wkv_compress_groups_profiled.argtypes = l.wkv_compress_groups.argtypes + [C.POINTER(C.c_float)]
+    l.wkv_compress_groups_profiled.restype = C.c_int
     l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
     l.wkv_group_budgets.restype = C.c_int
     l.wkv_status_string.argtypes = [C.c_int]; l.wkv_status_string.restype = C.c_char_p
@@ -182,9 +186,16 @@ class CompressCall:
                       _ptr_array(v_layers), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
                       _ptr(win_idx_out), _ptr(tok_idx_out), _ptr(n_keep_out), _ptr(workspace), ws_bytes)
         self._fn = lib().wkv_compress_groups
+        self._fn_profiled = lib().wkv_compress_groups_profiled
 
     def __call__(self, stream=None) -> None:
         _check(self._fn(*self._args, _stream(stream)))
+
+    def profiled(self, stream=None) -> List[float]:
+        """``wkv_compress_groups_profiled``: the same call, returning per-kernel milliseconds."""
+        ms = (C.c_float * WKV_N_STAGES)()
+        _check(self._fn_profiled(*self._args, _stream(stream), ms))
+        return list(ms)
 
 
 def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers,

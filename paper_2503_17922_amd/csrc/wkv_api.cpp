@@ -119,11 +119,12 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers, const 
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_gather_group launch");
 }
 
-wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
-                               const void *const *q_obs_groups, const void *const *k_layers,
-                               const void *const *v_layers, void *const *k_out_layers,
-                               void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
-                               int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                                const void *const *q_obs_groups, const void *const *k_layers,
+                                const void *const *v_layers, void *const *k_out_layers,
+                                void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
+                                int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                hipEvent_t *ev /* null or [WKV_N_STAGES + 1] */) {
   Prepared pr;
   wkv_status st = prepare(problem, &pr);
   if (st != WKV_OK) return st;
@@ -152,15 +153,64 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
   st = check_workspace(pr.shape, pl, n_groups, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;
   hipStream_t stream = (hipStream_t)hip_stream;
-  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, ws.t, stream);
+  hipError_t e;
+#define WKV_MARK(i) if (ev && (e = hipEventRecord(ev[i], stream)) != hipSuccess) return hip_fail(e, "event record");
+  WKV_MARK(0)
+  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, ws.t, stream, ev ? ev[1] : nullptr);
   if (e != hipSuccess) return hip_fail(e, "score launch");
+  WKV_MARK(2)
   e = launch_pool(pr.shape, pr.bp, n_groups, ws.t, ws.s, stream);
   if (e != hipSuccess) return hip_fail(e, "pool launch");
+  WKV_MARK(3)
   e = launch_topk(pr.shape, pr.bp, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "top-k launch");
+  WKV_MARK(4)
   e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "gather launch");
+  WKV_MARK(5)
+#undef WKV_MARK
   return WKV_OK;
+}
+
+wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                               const void *const *q_obs_groups, const void *const *k_layers,
+                               const void *const *v_layers, void *const *k_out_layers,
+                               void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
+                               int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return compress_impl(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
+                       win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
+                                        const void *const *q_obs_groups, const void *const *k_layers,
+                                        const void *const *v_layers, void *const *k_out_layers,
+                                        void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
+                                        int32_t *n_keep_out, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream, float *stage_ms_out) {
+  if (!stage_ms_out) { set_error("stage_ms_out is NULL"); return WKV_ERR_INVALID_ARG; }
+  hipEvent_t ev[WKV_N_STAGES + 1];
+  int made = 0;
+  hipError_t e = hipSuccess;
+  for (; made < WKV_N_STAGES + 1; ++made)
+    if ((e = hipEventCreate(&ev[made])) != hipSuccess) break;
+  wkv_status st = WKV_OK;
+  if (e != hipSuccess) {
+    st = hip_fail(e, "hipEventCreate");
+  } else {
+    st = compress_impl(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
+                       win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, ev);
+    if (st == WKV_OK) {
+      if ((e = hipEventSynchronize(ev[WKV_N_STAGES])) != hipSuccess) st = hip_fail(e, "hipEventSynchronize");
+      for (int i = 0; st == WKV_OK && i < WKV_N_STAGES; ++i)
+        if ((e = hipEventElapsedTime(&stage_ms_out[i], ev[i], ev[i + 1])) != hipSuccess) {
+          // an event that was never recorded (a stage with nothing to launch) reads as 0
+          stage_ms_out[i] = 0.0f;
+          (void)hipGetLastError();
+        }
+    }
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
 }
 
 }  // extern "C"

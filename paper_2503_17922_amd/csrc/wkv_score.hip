@@ -374,12 +374,14 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
 // =========================================================================================
 template <int D, int MT>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                              int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream) {
+                              int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream,
+                              hipEvent_t mid) {
   dim3 block(MF_THREADS);
   dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, t_out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
   if (s.t_stride <= 0) return hipSuccess;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl, partials, t_out);
@@ -388,7 +390,8 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
 
 template <typename T, int D>
 static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                                 int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream) {
+                                 int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream,
+                                 hipEvent_t mid) {
   int R = 1;
   while (R < pl.m_pad) R <<= 1;
   dim3 block(GEN_THREADS);
@@ -396,6 +399,7 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
   hipLaunchKernelGGL((stats_generic_kernel<T, D>), g1, block, 0, stream, s, bp, gp, pl, partials, R);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
   if (s.t_stride <= 0) return hipSuccess;
   const size_t lds = ((size_t)s.M * D + s.M) * sizeof(float);
   static bool attr_set = false;
@@ -411,22 +415,22 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
 }
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                        int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream) {
+                        int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream, hipEvent_t mid) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
 #define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, partials, t_out, stream);
+  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
     WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
     WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
 #undef WKV_MFMA_CASE
     return hipErrorInvalidValue;
   }
   if (s.dtype == WKV_BF16) {
-    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream);
-    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream);
+    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
+    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
   }
-  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream);
-  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream);
+  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
+  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
 }
 
 }  // namespace wkv

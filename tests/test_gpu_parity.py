@@ -48,7 +48,8 @@ def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check
     t_dev, s_dev, wi, ti, nk = st.stages(g0)
     assert np.array_equal(wi.cpu().numpy()[..., : st.dims.k_max], win_idx[g0]) and np.array_equal(ti.cpu().numpy(), tok_idx[g0])
     assert np.array_equal(nk.cpu().numpy(), n_keep[g0])
-    t_host = t_dev.cpu().numpy().astype(np.float64); s_host = s_dev.cpu().numpy().astype(np.float64)
+    t_host = t_dev.cpu().numpy().astype(np.float64)[..., : st.dims.t_stride]
+    s_host = s_dev.cpu().numpy().astype(np.float64)[..., : st.dims.nw_max]
 
     # ---- structure of every index row -------------------------------------------------------------
     sels = {}
@@ -239,7 +240,8 @@ def test_window_pool_alone(device):
         prob = W.Problem(n_q_heads=2, n_kv_heads=2, head_dim=64, w_obs=a, seq_len=[L], win=[win], top_p=[p],
                          k_windows=[0], dtype=W.WKV_BF16)
         t = rng.random((1, 2, L - a)).astype(np.float32)
-        t[0, 1, ::3] = t[0, 1, 1::3][: len(t[0, 1, ::3])]      # repeated values inside windows
+        m = len(t[0, 1, 1::3])
+        t[0, 1, ::3][:m] = t[0, 1, 1::3]                       # repeated values inside windows
         nw = -(-(L - a) // win)
         s_dev = torch.empty((1, 2, nw), dtype=torch.float32, device=device)
         W.wkv_window_pool(prob, torch.from_numpy(t).to(device), s_dev)
