@@ -15,47 +15,15 @@
 //                   t_j = sum_i 2^(v_ij - lse2_i).
 //
 // Two kernel families implement the passes:
-//   * MFMA (bf16 inputs, M <= 128): v_mfma_f32_16x16x32_bf16 with the query rows as the A
-//     operand (fragments pre-arranged in LDS, one conflict-free ds_read_b128 per fragment) and
-//     the keys as the B operand, loaded straight from global memory into registers in
-//     operand layout (lane = key l%16, 16-byte piece l/16 of a 64-byte run), so K never
-//     passes through LDS and the four waves of a workgroup never synchronise in the loop.
-//     In the 16x16 result layout a lane holds 4 rows of one key column: the column sums of
-//     Eq. 2 are in-lane adds plus two cross-lane steps, and per-row statistics are kept
-//     per lane and only merged once per chunk.
+//   * MFMA (bf16 inputs, M <= 128): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
+//     loaded straight from global memory into registers in operand layout, so K never passes
+//     through LDS and the four waves of a workgroup never synchronise in the loop; the
+//     query rows are the B operand, read as pre-arranged fragments from LDS.
 //   * generic (fp32 inputs, or M > 128): plain fp32 FMAs, thread-per-row for the stats,
 //     thread-per-key for the scores, the other operand broadcast from LDS.
-#include "wkv_internal.h"
+#include "wkv_device.h"
 
 namespace wkv {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-
-__device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// Merge (m2, z2) into (m, z): both describe sum 2^(v - m) over disjoint key sets.
-__device__ __forceinline__ void merge_stats(float &m, float &z, float m2, float z2) {
-  const float mn = fmaxf(m, m2);
-  if (mn == -INFINITY) { m = mn; z = 0.0f; return; }
-  z = z * fast_exp2(m - mn) + z2 * fast_exp2(m2 - mn);
-  m = mn;
-}
-
-// lse2 of one row from its per-chunk partials.
-__device__ __forceinline__ float fold_partials(const float2 *__restrict__ part, int n_chunks) {
-  float m = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, part[c].x);
-  float z = 0.0f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const float2 pz = part[c];
-    if (pz.x != -INFINITY) z += pz.y * fast_exp2(pz.x - m);
-  }
-  return m + fast_log2(z);
-}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -177,38 +145,29 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
 // =========================================================================================
 // MFMA kernels (bf16)
 // =========================================================================================
-constexpr int MF_THREADS = 256;
-constexpr int MF_WAVES = 4;
-constexpr int MF_NT = 2;        // key tiles of 16 that share one A-fragment read
-constexpr float MF_RESCALE = 16.0f;   // re-reference a row when a logit exceeds its reference by 2^16
-
-// Arrange the M query rows of KV head h as MFMA A fragments in LDS.
-// Fragment (mt, ks) is 64 x 16 bytes: lane l holds row 16*mt + l%16, channels 32*ks + 8*(l/16)..+7.
-template <int D, int MT>
-__device__ __forceinline__ void stage_q_fragments(const Shape &s, const void *qbase, int b, int h, uint4 *qfrag) {
-  constexpr int KS = D / 32;
-  for (int i = threadIdx.x; i < MT * KS * 64; i += MF_THREADS) {
-    const int l = i & 63, f = i >> 6, ks = f % KS, mt = f / KS;
-    const int r = mt * 16 + (l & 15);
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r < s.M) {
-      const int hq = h * s.G + r / s.w_obs, io = r % s.w_obs;
-      const int64_t off = (int64_t)b * s.q_sb + (int64_t)hq * s.q_sh + (int64_t)io * s.q_st + ks * 32 + (l >> 4) * 8;
-      v = *(const uint4 *)((const uint16_t *)qbase + off);
-    }
-    qfrag[i] = v;
-  }
-}
-
+// Orientation: D[key, query row] = sum_c K[key, c] * Q[row, c].  The keys are the A operand (16
+// keys x 32 channels per instruction, loaded straight from global memory: lane l holds key
+// l%16, the 16-byte piece l/16 of a 64-byte run, so the four lanes of a key read 64 contiguous
+// bytes), the stacked query rows are the B operand (fragments pre-arranged in LDS, one
+// conflict-free ds_read_b128 each).  In the 16x16 result a lane holds 4 consecutive keys of
+// ONE query row per row tile, so a lane needs only MT row constants (reference / lse2), the
+// row statistics of pass 1 are in-lane accumulations merged once per chunk, and the column
+// sums of pass 2 are in-lane adds over the row tiles plus one 16-lane DPP reduction.
 // PASS 1: stats.  PASS 2: scores.
 template <int D, int MT, int PASS>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    float *__restrict__ t_out) {
   constexpr int KS = D / 32;
+  constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
   __shared__ uint4 qfrag[MT * KS * 64];
   __shared__ float lse_s[MT * 16];
   __shared__ float2 wave_part[MF_WAVES][MT * 16];
+  __shared__ float2 fold_s[PASS == 2 ? MF_THREADS / (MT * 16) : 1][MT * 16];
+  // Pass 2 collects the chunk's token scores here and writes them out once at the end: global
+  // stores inside the loop would share the vector-memory counter with the key prefetch and make
+  // every wait for keys also wait for store acknowledgements.
+  __shared__ float t_s[PASS == 2 ? MF_MAX_CHUNK : 1];
 
   const int bh = blockIdx.y, b = bh / s.Hkv, h = bh % s.Hkv, g = blockIdx.z;
   const int L = bp.seq[b].L;
@@ -219,147 +178,174 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
 
   const int chunk = PASS == 1 ? pl.chunk1 : pl.chunk2;
   const int c0 = blockIdx.x * chunk;
-  const int limit = PASS == 1 ? L : n_review;       // keys that matter to this pass
+  const int limit = PASS == 1 ? L : n_review;         // keys that matter to this pass
   float *trow = PASS == 2 ? t_out + row * s.t_stride : nullptr;
 
   if (PASS == 2) {
-    const int cend = min(c0 + chunk, s.t_stride);
+    const int cend_fill = min(c0 + chunk, s.t_stride);
     if (c0 >= n_review) {
-      for (int j = c0 + threadIdx.x; j < cend; j += MF_THREADS) trow[j] = 0.0f;
+      for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
       return;
     }
-    // zero fill of the part of this chunk that lies beyond the review context
-    for (int j = max(c0, n_review) + threadIdx.x; j < cend; j += MF_THREADS) trow[j] = 0.0f;
-    for (int r = threadIdx.x; r < MT * 16; r += MF_THREADS)
-      lse_s[r] = r < s.M ? fold_partials(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1) : INFINITY;
+    // lse2 of every row: MF_THREADS / (MT*16) threads share a row's partials
+    constexpr int ROWS = MT * 16, TPR = MF_THREADS / ROWS;
+    const int r = threadIdx.x % ROWS, part_id = threadIdx.x / ROWS;
+    float m = -INFINITY, z = 0.0f;
+    if (r < s.M)
+      fold_partials_strided(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1, part_id, TPR, m, z);
+    fold_s[part_id][r] = make_float2(m, z);
+    __syncthreads();
+    if (threadIdx.x < ROWS) {
+      for (int i = 1; i < TPR; ++i) merge_stats(m, z, fold_s[i][r].x, fold_s[i][r].y);
+      lse_s[r] = r < s.M ? m + fast_log2(z) : INFINITY;
+    }
   }
   stage_q_fragments<D, MT>(s, gp.q[g], b, h, qfrag);
   __syncthreads();
 
-  // per-lane row constants: rows 16*mt + 4*quad + e
-  float lse_r[MT][4];
-  float mref[MT][4], zsum[MT][4];
+  // per-lane row constants: this lane's query row of row tile mt is 16*mt + col
+  float lse_r[MT], mref[MT], zsum[MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = mt * 16 + quad * 4 + e;
-      if (PASS == 2) lse_r[mt][e] = lse_s[r];
-      mref[mt][e] = -INFINITY;
-      zsum[mt][e] = 0.0f;
-    }
+  for (int mt = 0; mt < MT; ++mt) {
+    lse_r[mt] = PASS == 2 ? lse_s[mt * 16 + col] : 0.0f;
+    mref[mt] = -INFINITY;
+    zsum[mt] = 0.0f;
+  }
 
   const int cend = min(c0 + chunk, limit);
   const uint16_t *kbase = (const uint16_t *)gp.k[g] + (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh + quad * 8;
-  constexpr int STEP = 16 * MF_NT;                    // keys per wave iteration
+  const float c1 = s.c1;
 
-  for (int j0 = c0 + wave * STEP; j0 < cend; j0 += MF_WAVES * STEP) {
-    // ---- load the key fragments of MF_NT tiles (rows clamped into the sequence) ----------
-    bf16x8 kf[MF_NT][KS];
+  // One wave iteration: prefetch the keys of the next iteration into `kn`, compute on `kf`.
+  // The loop below calls it with the two buffers swapped in turn, so no register copies are
+  // needed and the wait for a buffer sits a whole iteration after its loads were issued.
+  auto iteration = [&](const KFrags<KS> &kf, KFrags<KS> &kn, const int j0) __attribute__((always_inline)) {
+    // The query fragments are loop invariant; without this barrier the compiler hoists all of
+    // them into registers (128 VGPRs) and spills.  They are meant to be re-read from LDS.
+    asm volatile("" ::: "memory");
+    // ---- prefetch the next iteration's keys while this one is computed --------------------
+    // Unconditional: a prefetch behind a branch makes every wait for `kf` also wait for it.
+    // Past the end of the chunk the row index clamps to the chunk's last key (a cache hit).
+    load_k<KS>(kn, kbase, s.kv_st, j0 + MF_WAVES * STEP, col, cend);
+
+    // ---- logits: acc[n][mt][e] = k_{j0+16n+4*quad+e} . q_{16*mt+col} -----------------------
+    f32x4 acc[MF_KT][MT];
 #pragma unroll
-    for (int n = 0; n < MF_NT; ++n) {
-      const int j = min(j0 + n * 16 + col, L - 1);
-      const uint16_t *kp = kbase + (int64_t)j * s.kv_st;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[n][ks] = *(const bf16x8 *)(kp + ks * 32);
-    }
-    // ---- logits: acc[n][mt] = Q_mt . K_n^T -------------------------------------------------
-    f32x4 acc[MF_NT][MT];
-#pragma unroll
-    for (int n = 0; n < MF_NT; ++n)
+    for (int n = 0; n < MF_KT; ++n)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const uint4 araw = qfrag[(mt * KS + ks) * 64 + lane];
-        const bf16x8 a = *(const bf16x8 *)&araw;
+        const uint4 qraw = qfrag[(mt * KS + ks) * 64 + lane];
+        const bf16x8 qb = *(const bf16x8 *)&qraw;
 #pragma unroll
-        for (int n = 0; n < MF_NT; ++n)
-          acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kf[n][ks], acc[n][mt], 0, 0, 0);
+        for (int n = 0; n < MF_KT; ++n)
+          acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.f[n][ks], qb, acc[n][mt], 0, 0, 0);
       }
 
     if (PASS == 1) {
-      // base-2 logits, masked where the key is beyond the sequence or not visible to the row
-      const bool tail = j0 + STEP > n_review;          // wave-uniform
-      bool need = false;
+      if (j0 + STEP > n_review) {
+        // tiles that touch the observation block: causal mask (key j visible to observation
+        // query io iff j <= n_review + io) and the end of the sequence
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+          const int r = mt * 16 + col;
+          const int last_vis = r < s.M ? n_review + (r % s.w_obs) : -1;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float vmax = -INFINITY;
+          for (int n = 0; n < MF_KT; ++n)
 #pragma unroll
-          for (int n = 0; n < MF_NT; ++n) {
-            float v = acc[n][mt][e] * s.c1;
-            if (tail) {   // rare: only the tiles that touch the observation block
-              const int j = j0 + n * 16 + col;
-              const int r = mt * 16 + quad * 4 + e;
-              const int last_vis = r < s.M ? n_review + (r % s.w_obs) : -1;
-              if (j > last_vis || j >= cend) v = -INFINITY;
+            for (int e = 0; e < 4; ++e) {
+              const int j = j0 + n * 16 + quad * 4 + e;
+              if (j > last_vis || j >= cend) acc[n][mt][e] = -INFINITY;
             }
-            acc[n][mt][e] = v;
-            vmax = fmaxf(vmax, v);
-          }
-          need |= vmax > mref[mt][e] + MF_RESCALE;
         }
-      if (__any(need)) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float vmax = mref[mt][e];
-#pragma unroll
-            for (int n = 0; n < MF_NT; ++n) vmax = fmaxf(vmax, acc[n][mt][e]);
-            if (vmax > mref[mt][e]) {
-              zsum[mt][e] *= fast_exp2(mref[mt][e] - vmax);   // mref = -inf gives 0
-              mref[mt][e] = vmax;
-            }
-          }
       }
+      // z += sum 2^(v - mref).  A sum that is huge, infinite or NaN (first tile: mref = -inf)
+      // means a logit far above the row's reference: re-reference the row and redo the tile.
+      float psum[MT];
+      bool redo = false;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int n = 0; n < MF_NT; ++n)
-            if (mref[mt][e] != -INFINITY) zsum[mt][e] += fast_exp2(acc[n][mt][e] - mref[mt][e]);
-    } else {
-      float tsum[MF_NT];
-#pragma unroll
-      for (int n = 0; n < MF_NT; ++n) {
+      for (int mt = 0; mt < MT; ++mt) {
         float a = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int n = 0; n < MF_KT; ++n)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) a += fast_exp2(fmaf(acc[n][mt][e], s.c1, -lse_r[mt][e]));
-        a += __shfl_xor(a, 16);
-        a += __shfl_xor(a, 32);
-        tsum[n] = a;
+          for (int e = 0; e < 4; ++e) a += fast_exp2(fmaf(acc[n][mt][e], c1, -mref[mt]));
+        psum[mt] = a;
+        redo |= !(a <= MF_BIG);
       }
-      // quad n writes tile n: 16 consecutive floats per tile
+      if (__any(redo)) {
 #pragma unroll
-      for (int n = 0; n < MF_NT; ++n) {
-        const int j = j0 + n * 16 + col;
-        if (quad == n && j < cend) trow[j] = tsum[n];
+        for (int mt = 0; mt < MT; ++mt) {
+          if (!(psum[mt] <= MF_BIG)) {
+            float vmax = -INFINITY;
+#pragma unroll
+            for (int n = 0; n < MF_KT; ++n)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) vmax = fmaxf(vmax, acc[n][mt][e]);
+            const float nref = fmaxf(mref[mt], vmax * c1);
+            float a = 0.0f;
+            if (nref != -INFINITY) {
+              zsum[mt] *= fast_exp2(mref[mt] - nref);      // mref = -inf: 2^-inf = 0 and zsum is 0
+              mref[mt] = nref;
+#pragma unroll
+              for (int n = 0; n < MF_KT; ++n)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a += fast_exp2(fmaf(acc[n][mt][e], c1, -nref));
+            }
+            psum[mt] = a;
+          }
+        }
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) zsum[mt] += psum[mt];
+    } else {
+      // t_j = sum over this lane's MT rows, then over the 16 lanes (rows 16*mt + 0..15)
+#pragma unroll
+      for (int n = 0; n < MF_KT; ++n) {
+        f32x4 tq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float a = 0.0f;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) a += fast_exp2(fmaf(acc[n][mt][e], c1, -lse_r[mt]));
+          tq[e] = row16_sum(a);
+        }
+        if (col == 0) *(f32x4 *)(t_s + (j0 - c0) + n * 16 + quad * 4) = tq;   // 4 consecutive keys per quad
       }
     }
+  };
+
+  int j0 = c0 + wave * STEP;
+  KFrags<KS> ka, kb;
+  load_k<KS>(ka, kbase, s.kv_st, j0, col, max(cend, 1));
+  while (j0 < cend) {
+    iteration(ka, kb, j0);
+    j0 += MF_WAVES * STEP;
+    if (j0 >= cend) break;
+    iteration(kb, ka, j0);
+    j0 += MF_WAVES * STEP;
   }
 
+  if (PASS == 2) {
+    __syncthreads();
+    const int cend_fill = min(c0 + chunk, s.t_stride);
+    for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
+  }
   if (PASS == 1) {
-    // merge the 16 key columns of each row (lanes with equal quad), then the 4 waves
+    // merge the 4 quads of each row (lanes col, col+16, col+32, col+48), then the 4 waves
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      float m = mref[mt], z = zsum[mt];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float m = mref[mt][e], z = zsum[mt][e];
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-          const float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
-          merge_stats(m, z, m2, z2);
-        }
-        if (col == 0) wave_part[wave][mt * 16 + quad * 4 + e] = make_float2(m, z);
+      for (int off = 16; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
+        merge_stats(m, z, m2, z2);
       }
+      if (quad == 0) wave_part[wave][mt * 16 + col] = make_float2(m, z);
+    }
     __syncthreads();
     for (int r = threadIdx.x; r < pl.m_pad; r += MF_THREADS) {   // m_pad <= MT*16
       float m = wave_part[0][r].x, z = wave_part[0][r].y;
