@@ -180,9 +180,9 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
  * stream, and reports each kernel's duration.  It creates and destroys HIP events and blocks
  * the calling thread, so it is for benchmarks and profiling, not for serving.
  *   stage_ms_out  host float [WKV_N_STAGES]: milliseconds of, in order, the softmax-statistics
- *                 pass (Eq. 1; with the single-pass score kernel: the clearing of its sync block), the
- *                 score pass (Eq. 1-2), window pooling (Eq. 3-4), top-k
- *                 selection (2.2.1) and the shared-index gather (2.2.2).
+ *                 pass (Eq. 1), the score pass (Eq. 1-2), window pooling (Eq. 3-4; 0 here, because
+ *                 this call pools inside the selection kernel), pooling + top-k selection
+ *                 (2.2.1) and the shared-index gather (2.2.2).
  */
 #define WKV_N_STAGES 5
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
@@ -201,13 +201,6 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
  */
 wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
                              double *budgets_out);
-
-/*
- * Diagnostic knob (host state, process wide): mode 1 makes wkv_score and wkv_compress_groups
- * always use the two-pass score kernels; mode 0 (default) lets them choose the single-pass
- * kernel when the shape and the device allow it.  Results obey the same contract either way.
- */
-void wkv_debug_set_score_path(int32_t mode);
 
 const char *wkv_status_string(wkv_status status);
 

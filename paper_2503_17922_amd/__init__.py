@@ -22,7 +22,7 @@ WKV_N_STAGES = 5
 STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
 
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
-           "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_debug_set_score_path", "wkv_status_string",
+           "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string",
            "wkv_last_error")
 
 
@@ -78,7 +78,6 @@ def lib() -> C.CDLL:
     l.wkv_compress_groups_profiled.restype = C.c_int
     l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
     l.wkv_group_budgets.restype = C.c_int
-    l.wkv_debug_set_score_path.argtypes = [C.c_int32]; l.wkv_debug_set_score_path.restype = None
     l.wkv_status_string.argtypes = [C.c_int]; l.wkv_status_string.restype = C.c_char_p
     l.wkv_last_error.argtypes = []; l.wkv_last_error.restype = C.c_char_p
     _lib = l
@@ -210,6 +209,3 @@ def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:
     _check(lib().wkv_group_budgets(b_total, n_groups, lam, out))
     return list(out)[:n_groups]
 
-
-def wkv_debug_set_score_path(mode: int) -> None:
-    lib().wkv_debug_set_score_path(mode)

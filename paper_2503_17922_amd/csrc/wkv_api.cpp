@@ -40,19 +40,6 @@ wkv_status check_workspace(const Shape &s, const ScorePlan &pl, int32_t n_groups
   return WKV_OK;
 }
 
-// Token scores by the single-pass kernel when the shape and the device allow it, else by the
-// two-pass kernels.  `mid` (optional) is recorded between the two launches of either variant.
-hipError_t run_score(const Prepared &pr, const ScorePlan &pl, const GroupPtrs &gp, int32_t n_groups,
-                     const Workspace &ws, float *t_out, hipStream_t stream, hipEvent_t mid) {
-  const FusedPlan fp = plan_fused(pr.shape, pr.bp, pl, n_groups);
-  if (fp.eligible) {
-    bool used = false;
-    hipError_t e = launch_score_fused(pr.shape, pr.bp, pl, fp, gp, ws.sync, ws.sync_words, t_out, stream, mid, &used);
-    if (e != hipSuccess || used) return e;
-  }
-  return launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, t_out, stream, mid);
-}
-
 }  // namespace
 
 extern "C" {
@@ -71,7 +58,7 @@ wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *
   GroupPtrs gp;
   std::memset(&gp, 0, sizeof(gp));
   gp.q[0] = q_obs; gp.k[0] = k_first;
-  hipError_t e = run_score(pr, pl, gp, 1, ws, t_out, (hipStream_t)hip_stream, nullptr);
+  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, ws.partials, ws.lse, t_out, (hipStream_t)hip_stream);
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_score launch");
 }
 
@@ -169,14 +156,12 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
   hipError_t e;
 #define WKV_MARK(i) if (ev && (e = hipEventRecord(ev[i], stream)) != hipSuccess) return hip_fail(e, "event record");
   WKV_MARK(0)
-  e = run_score(pr, pl, gp, n_groups, ws, ws.t, stream, ev ? ev[1] : nullptr);
+  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, ws.lse, ws.t, stream, ev ? ev[1] : nullptr);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
-  e = launch_pool(pr.shape, pr.bp, n_groups, ws.t, ws.s, stream);
-  if (e != hipSuccess) return hip_fail(e, "pool launch");
-  WKV_MARK(3)
-  e = launch_topk(pr.shape, pr.bp, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
-  if (e != hipSuccess) return hip_fail(e, "top-k launch");
+  WKV_MARK(3)     // pooling runs inside the selection kernel here: its own slot stays empty
+  e = launch_select(pr.shape, pr.bp, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
+  if (e != hipSuccess) return hip_fail(e, "select launch");
   WKV_MARK(4)
   e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "gather launch");

@@ -140,25 +140,6 @@ ScorePlan plan_score(const Shape &s, int32_t n_groups) {
   return pl;
 }
 
-FusedPlan plan_fused(const Shape &s, const BatchParams &bp, const ScorePlan &pl, int32_t n_groups) {
-  FusedPlan fp;
-  std::memset(&fp, 0, sizeof(fp));
-  int64_t per_group = 0;
-  for (int b = 0; b < s.B; ++b) {
-    fp.nch[b] = (int32_t)ceil_div(bp.seq[b].L, FUSED_CHUNK);
-    fp.first[b] = (int32_t)per_group;
-    per_group += (int64_t)s.Hkv * fp.nch[b];
-  }
-  fp.first[s.B] = (int32_t)per_group;
-  fp.tickets_per_group = (int32_t)per_group;
-  fp.total_tickets = (int32_t)(per_group * n_groups);
-  fp.eligible = pl.mfma && per_group * n_groups < (int64_t)1 << 30 && score_path_override() == 2;
-  return fp;
-}
-
-static int g_score_path = 0;
-int score_path_override() { return g_score_path; }
-
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base) {
@@ -167,14 +148,13 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_group
   const size_t part = align256(rows * plan.m_pad * plan.n_chunks1 * sizeof(float2));
   const size_t tb = align256(rows * (size_t)(s.t_stride > 0 ? s.t_stride : 1) * sizeof(float));
   const size_t sb = align256(rows * (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(float));
-  w.sync_words = SYNC_HEADER_WORDS + rows * SYNC_PROBLEM_WORDS;
-  const size_t yb = align256(w.sync_words * sizeof(uint32_t));
+  const size_t lb = align256(rows * plan.m_pad * sizeof(float));
   char *b = (char *)base;
   w.partials = (float2 *)b;
   w.t = (float *)(b + part);
   w.s = (float *)(b + part + tb);
-  w.sync = (uint32_t *)(b + part + tb + sb);
-  w.bytes = part + tb + sb + yb;
+  w.lse = (float *)(b + part + tb + sb);
+  w.bytes = part + tb + sb + lb;
   return w;
 }
 
@@ -212,8 +192,6 @@ wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda, do
   for (int32_t h = 0; h < n_groups; ++h) budgets_out[h] = bottom - step * (double)h;
   return WKV_OK;
 }
-
-void wkv_debug_set_score_path(int32_t mode) { g_score_path = (mode == 1 || mode == 2) ? mode : 0; }
 
 const char *wkv_status_string(wkv_status st) {
   switch (st) {

@@ -10,9 +10,8 @@
 //   pass 1 (stats)  per (row, key chunk): running maximum m and sum z = sum 2^(v - m) of the
 //                   base-2 logits v = (q.k) * scale * log2(e), with the causal mask of the
 //                   observation block applied.  Partials go to the workspace.
-//   pass 2 (score)  each workgroup folds the partials of its KV head into one
-//                   lse2_i = m_i + log2(z_i) per row, recomputes its logits and writes
-//                   t_j = sum_i 2^(v_ij - lse2_i).
+//   fold            one tiny launch turns the partials of every row into lse2_i = m_i + log2(z_i).
+//   pass 2 (score)  each workgroup recomputes its logits and writes t_j = sum_i 2^(v_ij - lse2_i).
 //
 // Two kernel families implement the passes:
 //   * MFMA (bf16 inputs, M <= 128): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
@@ -32,6 +31,33 @@ template <> struct Elem<float> {
 template <> struct Elem<uint16_t> {
   static __device__ __forceinline__ float load(const void *p, int64_t i) { return bf16_to_float(((const uint16_t *)p)[i]); }
 };
+
+// =========================================================================================
+// fold: per-chunk (m, z) partials of pass 1 -> one lse2 per row, once per (group, sequence, KV head)
+// =========================================================================================
+constexpr int FOLD_THREADS = 256;
+
+__global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(Shape s, ScorePlan pl, const float2 *__restrict__ partials,
+                                                            float *__restrict__ lse) {
+  __shared__ float2 part_s[FOLD_THREADS];
+  const int64_t row = (int64_t)blockIdx.y * s.B * s.Hkv + blockIdx.x;
+  // TPR threads share a row; rows are handled in passes of FOLD_THREADS / TPR
+  const int TPR = pl.m_pad >= 128 ? 2 : (pl.m_pad >= 64 ? 4 : 8);
+  const int rows_per_pass = FOLD_THREADS / TPR;
+  for (int r0 = 0; r0 < pl.m_pad; r0 += rows_per_pass) {
+    const int r = r0 + threadIdx.x % rows_per_pass, part_id = threadIdx.x / rows_per_pass;
+    float m = -INFINITY, z = 0.0f;
+    if (r < s.M)
+      fold_partials_strided(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1, part_id, TPR, m, z);
+    __syncthreads();
+    part_s[threadIdx.x] = make_float2(m, z);
+    __syncthreads();
+    if (part_id == 0 && r < pl.m_pad) {
+      for (int i = 1; i < TPR; ++i) merge_stats(m, z, part_s[i * rows_per_pass + threadIdx.x].x, part_s[i * rows_per_pass + threadIdx.x].y);
+      lse[row * pl.m_pad + r] = r < s.M ? m + fast_log2(z) : INFINITY;   // padded rows: 2^-inf = 0
+    }
+  }
+}
 
 // =========================================================================================
 // generic kernels
@@ -101,7 +127,7 @@ __global__ __launch_bounds__(GEN_THREADS) void stats_generic_kernel(Shape s, Bat
 template <typename T, int D>
 __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                     ScorePlan pl,
-                                                                    const float2 *__restrict__ partials,
+                                                                    const float *__restrict__ lse_g,
                                                                     float *__restrict__ t_out) {
   extern __shared__ float smem[];            // q [M][D], then lse2 [M]
   float *qs = smem;
@@ -121,8 +147,7 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
     const int hq = h * s.G + r / s.w_obs, io = r % s.w_obs;
     qs[i] = Elem<T>::load(gp.q[g], (int64_t)b * s.q_sb + (int64_t)hq * s.q_sh + (int64_t)io * s.q_st + c);
   }
-  for (int r = threadIdx.x; r < s.M; r += GEN_THREADS)
-    lse[r] = fold_partials(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1);
+  for (int r = threadIdx.x; r < s.M; r += GEN_THREADS) lse[r] = lse_g[row * pl.m_pad + r];
   __syncthreads();
   const int64_t koff = (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh;
   for (int j = c0 + threadIdx.x; j < cend; j += GEN_THREADS) {
@@ -157,19 +182,23 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
 template <int D, int MT, int PASS>
 __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
+                                                                   const float *__restrict__ lse_g,
                                                                    float *__restrict__ t_out) {
   constexpr int KS = D / 32;
   constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
   __shared__ uint4 qfrag[MT * KS * 64];
-  __shared__ float lse_s[MT * 16];
-  __shared__ float2 wave_part[MF_WAVES][MT * 16];
-  __shared__ float2 fold_s[PASS == 2 ? MF_THREADS / (MT * 16) : 1][MT * 16];
+  __shared__ float2 wave_part[PASS == 1 ? MF_WAVES : 1][MT * 16];
   // Pass 2 collects the chunk's token scores here and writes them out once at the end: global
   // stores inside the loop would share the vector-memory counter with the key prefetch and make
   // every wait for keys also wait for store acknowledgements.
   __shared__ float t_s[PASS == 2 ? MF_MAX_CHUNK : 1];
 
-  const int bh = blockIdx.y, b = bh / s.Hkv, h = bh % s.Hkv, g = blockIdx.z;
+  // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
+  // are the ones most likely still held by the memory-side cache.
+  const int bx = PASS == 1 ? blockIdx.x : gridDim.x - 1 - blockIdx.x;
+  const int bh = PASS == 1 ? blockIdx.y : gridDim.y - 1 - blockIdx.y;
+  const int g = PASS == 1 ? blockIdx.z : gridDim.z - 1 - blockIdx.z;
+  const int b = bh / s.Hkv, h = bh % s.Hkv;
   const int L = bp.seq[b].L;
   const int n_review = L - s.w_obs;
   const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
@@ -177,7 +206,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
   const int col = lane & 15, quad = lane >> 4;
 
   const int chunk = PASS == 1 ? pl.chunk1 : pl.chunk2;
-  const int c0 = blockIdx.x * chunk;
+  const int c0 = bx * chunk;
   const int limit = PASS == 1 ? L : n_review;         // keys that matter to this pass
   float *trow = PASS == 2 ? t_out + row * s.t_stride : nullptr;
 
@@ -187,18 +216,6 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
       for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
       return;
     }
-    // lse2 of every row: MF_THREADS / (MT*16) threads share a row's partials
-    constexpr int ROWS = MT * 16, TPR = MF_THREADS / ROWS;
-    const int r = threadIdx.x % ROWS, part_id = threadIdx.x / ROWS;
-    float m = -INFINITY, z = 0.0f;
-    if (r < s.M)
-      fold_partials_strided(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1, part_id, TPR, m, z);
-    fold_s[part_id][r] = make_float2(m, z);
-    __syncthreads();
-    if (threadIdx.x < ROWS) {
-      for (int i = 1; i < TPR; ++i) merge_stats(m, z, fold_s[i][r].x, fold_s[i][r].y);
-      lse_s[r] = r < s.M ? m + fast_log2(z) : INFINITY;
-    }
   }
   stage_q_fragments<D, MT>(s, gp.q[g], b, h, qfrag);
   __syncthreads();
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
   float lse_r[MT], mref[MT], zsum[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    lse_r[mt] = PASS == 2 ? lse_s[mt * 16 + col] : 0.0f;
+    lse_r[mt] = PASS == 2 ? lse_g[row * pl.m_pad + min(mt * 16 + col, pl.m_pad - 1)] : 0.0f;
     mref[mt] = -INFINITY;
     zsum[mt] = 0.0f;
   }
@@ -350,7 +367,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
     for (int r = threadIdx.x; r < pl.m_pad; r += MF_THREADS) {   // m_pad <= MT*16
       float m = wave_part[0][r].x, z = wave_part[0][r].y;
       for (int w = 1; w < MF_WAVES; ++w) merge_stats(m, z, wave_part[w][r].x, wave_part[w][r].y);
-      partials[(row * pl.m_pad + r) * pl.n_chunks1 + blockIdx.x] = make_float2(m, z);
+      partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(m, z);
     }
   }
 }
@@ -360,23 +377,25 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
 // =========================================================================================
 template <int D, int MT>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                              int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream,
+                              int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
                               hipEvent_t mid) {
   dim3 block(MF_THREADS);
   dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, t_out);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
   if (s.t_stride <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl, partials, t_out);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
   return hipGetLastError();
 }
 
 template <typename T, int D>
 static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                                 int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream,
+                                 int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
                                  hipEvent_t mid) {
   int R = 1;
   while (R < pl.m_pad) R <<= 1;
@@ -387,6 +406,8 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
   if (e != hipSuccess) return e;
   if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
   if (s.t_stride <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   const size_t lds = ((size_t)s.M * D + s.M) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
@@ -396,27 +417,28 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
     attr_set = true;
   }
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_generic_kernel<T, D>), g2, block, lds, stream, s, bp, gp, pl, partials, t_out);
+  hipLaunchKernelGGL((score_generic_kernel<T, D>), g2, block, lds, stream, s, bp, gp, pl, lse, t_out);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                        int32_t n_groups, float2 *partials, float *t_out, hipStream_t stream, hipEvent_t mid) {
+                        int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
+                        hipEvent_t mid) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
 #define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
+  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
     WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
     WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
 #undef WKV_MFMA_CASE
     return hipErrorInvalidValue;
   }
   if (s.dtype == WKV_BF16) {
-    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
-    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
+    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
+    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
   }
-  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
-  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, partials, t_out, stream, mid);
+  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
+  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
 }
 
 }  // namespace wkv

@@ -74,12 +74,98 @@ __global__ __launch_bounds__(POOL_THREADS) void pool_kernel(Shape s, BatchParams
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Register-resident pooling for the common window sizes.  The window's token scores sit in
+// registers (loaded as float4s: a lane reads its window's 4*WIN contiguous bytes), the rank
+// counting is fully unrolled, nothing is indexed dynamically.
+// ------------------------------------------------------------------------------------------
+template <int WIN>
+__device__ __forceinline__ float pool_window_regs(const float *__restrict__ trow, int w, int n_review, int p) {
+  float v[WIN];
+  const int tok0 = w * WIN;
+  const int size = min(WIN, n_review - tok0);
+  if (size == WIN && ((uintptr_t)(trow + tok0) & 15) == 0) {
+#pragma unroll
+    for (int i = 0; i < WIN; i += 4) {
+      const float4 q = *(const float4 *)(trow + tok0 + i);
+      v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < WIN; ++i) v[i] = i < size ? trow[tok0 + i] : -INFINITY;
+  }
+  float acc = 0.0f;
+  if (p >= size) {
+#pragma unroll
+    for (int i = 0; i < WIN; ++i) acc += i < size ? v[i] : 0.0f;
+  } else {
+#pragma unroll
+    for (int i = 0; i < WIN; ++i) {
+      int rank = 0;
+#pragma unroll
+      for (int j = 0; j < WIN; ++j) rank += (v[j] > v[i]) || (v[j] == v[i] && j < i);
+      acc += (rank < p && i < size) ? v[i] : 0.0f;
+    }
+  }
+  return acc / (float)p;
+}
+
+// Any window size: plain loops over global memory (cached; O(size^2) compares).
+__device__ __forceinline__ float pool_window_any(const float *__restrict__ trow, int w, int win, int n_review, int p) {
+  const int tok0 = w * win;
+  const int size = min(win, n_review - tok0);
+  float acc = 0.0f;
+  if (p >= size) {
+    for (int i = 0; i < size; ++i) acc += trow[tok0 + i];
+  } else {
+    for (int i = 0; i < size; ++i) {
+      const float vi = trow[tok0 + i];
+      int rank = 0;
+      for (int j = 0; j < size; ++j) {
+        const float vj = trow[tok0 + j];
+        rank += (vj > vi) || (vj == vi && j < i);
+      }
+      if (rank < p) acc += vi;
+    }
+  }
+  return acc / (float)p;
+}
+
+// Window score by whichever of the two fits the window size (uniform per workgroup).
+__device__ __forceinline__ float pool_window(const float *__restrict__ trow, int w, int win, int n_review, int p) {
+  switch (win) {
+    case 8: return pool_window_regs<8>(trow, w, n_review, p);
+    case 16: return pool_window_regs<16>(trow, w, n_review, p);
+    case 32: return pool_window_regs<32>(trow, w, n_review, p);
+    default: return pool_window_any(trow, w, win, n_review, p);
+  }
+}
+
+// One thread per window; used when every sequence's window size has a register kernel.
+__global__ __launch_bounds__(POOL_THREADS) void pool_fast_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
+                                                                 float *__restrict__ s_out) {
+  const int bh = blockIdx.y, b = bh / s.Hkv, g = blockIdx.z;
+  const SeqParam sp = bp.seq[b];
+  const int n_review = sp.L - s.w_obs;
+  const int nw = (n_review + sp.win - 1) / sp.win;
+  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
+  const int w = blockIdx.x * POOL_THREADS + threadIdx.x;
+  if (w >= s.nw_max) return;
+  s_out[row * s.nw_max + w] = w < nw ? pool_window(t + row * s.t_stride, w, sp.win, n_review, sp.p) : -INFINITY;
+}
+
 hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
                        float *s_out, hipStream_t stream) {
   if (s.nw_max <= 0) return hipSuccess;
   const int wpb = POOL_THREADS;
   dim3 grid((s.nw_max + wpb - 1) / wpb, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL(pool_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out, wpb);
+  bool fast = true;
+  for (int b = 0; b < s.B; ++b) fast = fast && (bp.seq[b].win == 8 || bp.seq[b].win == 16 || bp.seq[b].win == 32);
+  if (fast)
+    hipLaunchKernelGGL(pool_fast_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out);
+  else
+    hipLaunchKernelGGL(pool_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out, wpb);
   return hipGetLastError();
 }
 
@@ -102,32 +188,24 @@ __device__ __forceinline__ uint32_t float_to_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams bp,
-                                                            const float *__restrict__ sc,
-                                                            int32_t *__restrict__ win_idx,
-                                                            int32_t *__restrict__ tok_idx,
-                                                            int32_t *__restrict__ n_keep) {
-  extern __shared__ uint32_t keys[];            // [nw_max], later reused for the selected list
+// Steps 2-4 on the keys already in LDS; `row` is the (group, sequence, KV head) index.
+__device__ __forceinline__ void topk_body(const Shape &s, const SeqParam sp, uint32_t *keys, int64_t row,
+                                          int32_t *__restrict__ win_idx, int32_t *__restrict__ tok_idx,
+                                          int32_t *__restrict__ n_keep) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sh_prefix, sh_remaining;
   __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
   __shared__ int run_gt, run_eq;
 
-  const int bh = blockIdx.x, b = bh / s.Hkv, g = blockIdx.y;
-  const SeqParam sp = bp.seq[b];
   const int n_review = sp.L - s.w_obs;
   const int nw = (n_review + sp.win - 1) / sp.win;
   const int k = sp.k;
-  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
-  const float *srow = sc + row * s.nw_max;
   int32_t *wrow = win_idx + row * s.k_max;
   int32_t *trow = tok_idx + row * s.nkeep_max;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  for (int w = tid; w < nw; w += TOPK_THREADS) keys[w] = float_to_key(srow[w]);
   if (tid == 0) { sh_prefix = 0u; sh_remaining = (uint32_t)k; }
   __syncthreads();
-
   // ---- 2. radix select -------------------------------------------------------------------
   uint32_t T = 0u, take_eq = 0u;
   if (k > 0) {
@@ -227,6 +305,38 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams
   if (tid == 0) n_keep[row] = nk;
 }
 
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams bp, const float *__restrict__ sc,
+                                                            int32_t *__restrict__ win_idx,
+                                                            int32_t *__restrict__ tok_idx,
+                                                            int32_t *__restrict__ n_keep) {
+  extern __shared__ uint32_t keys[];            // [nw_max], later reused for the selected list
+  const int bh = blockIdx.x, b = bh / s.Hkv, g = blockIdx.y;
+  const SeqParam sp = bp.seq[b];
+  const int nw = (sp.L - s.w_obs + sp.win - 1) / sp.win;
+  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
+  const float *srow = sc + row * s.nw_max;
+  for (int w = threadIdx.x; w < nw; w += TOPK_THREADS) keys[w] = float_to_key(srow[w]);
+  topk_body(s, sp, keys, row, win_idx, tok_idx, n_keep);
+}
+
+// Pooling and selection in one launch (the path wkv_compress_groups takes): the window scores
+// go straight from registers into the LDS key array and never touch global memory.
+__global__ __launch_bounds__(TOPK_THREADS) void select_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
+                                                              int32_t *__restrict__ win_idx,
+                                                              int32_t *__restrict__ tok_idx,
+                                                              int32_t *__restrict__ n_keep) {
+  extern __shared__ uint32_t keys[];
+  const int bh = blockIdx.x, b = bh / s.Hkv, g = blockIdx.y;
+  const SeqParam sp = bp.seq[b];
+  const int n_review = sp.L - s.w_obs;
+  const int nw = (n_review + sp.win - 1) / sp.win;
+  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
+  const float *trow = t + row * s.t_stride;
+  for (int w = threadIdx.x; w < nw; w += TOPK_THREADS)
+    keys[w] = float_to_key(pool_window(trow, w, sp.win, n_review, sp.p));
+  topk_body(s, sp, keys, row, win_idx, tok_idx, n_keep);
+}
+
 hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
                        int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
   const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
@@ -239,6 +349,21 @@ hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, 
   }
   dim3 grid(s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL(topk_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, sc, win_idx, tok_idx, n_keep);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
+                         int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
+  const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       WKV_MAX_WINDOWS * (int)sizeof(uint32_t));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(s.B * s.Hkv, n_groups);
+  hipLaunchKernelGGL(select_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, t, win_idx, tok_idx, n_keep);
   return hipGetLastError();
 }
 
