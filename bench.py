@@ -26,9 +26,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), scaled by the
-# same counters' reading for a plain copy of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE), each scaled by
+# what the same counter reads for a plain 256 MiB device copy (2.0 and 1.0 on this machine); the
+# runs are summarised in profiles/compress_groups_c4.md.  Missing key = not measured (null).
+MEASURED_TRAFFIC_BYTES = {
+    ("c4", "score_pre"): 562.5e6,      # statistics pass
+    ("c4", "score"): 564.0e6,          # fold + score pass
+    ("c4", "topk_windows"): 9.8e6,     # pooling + selection
+    ("c4", "gather"): 1083.2e6,
+    ("c4", "pipeline"): 2219.4e6,
+}
 
 
 def algorithmic_bytes(w):
@@ -104,6 +111,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (a known-size reference for hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
@@ -123,6 +132,14 @@ def main():
     call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, st.k, st.v, st.k_out, st.v_out,
                           st.win_idx, st.tok_idx, st.n_keep, st.workspace)
     stream = torch.cuda.current_stream().cuda_stream
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=device).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         call(stream)
