@@ -51,7 +51,7 @@ wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *
   if (st != WKV_OK) return st;
   if (!q_obs || !k_first || !t_out) { set_error("q_obs / k_first / t_out is NULL"); return WKV_ERR_INVALID_ARG; }
   if (misaligned(q_obs, 16) || misaligned(k_first, 16)) { set_error("q_obs and k_first must be 16-byte aligned"); return WKV_ERR_INVALID_ARG; }
-  const ScorePlan pl = plan_score(pr.shape, 1);
+  const ScorePlan pl = plan_score(pr.shape, pr.bp, 1);
   Workspace ws;
   st = check_workspace(pr.shape, pl, 1, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;
@@ -148,7 +148,7 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
     gp.q[g] = q_obs_groups[g];
     gp.k[g] = k_layers[(size_t)g * gamma];     // Section 2.2.2: the group's first layer is scored
   }
-  const ScorePlan pl = plan_score(pr.shape, n_groups);
+  const ScorePlan pl = plan_score(pr.shape, pr.bp, n_groups);
   Workspace ws;
   st = check_workspace(pr.shape, pl, n_groups, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;

@@ -51,7 +51,6 @@ __device__ __forceinline__ float fold_partials(const float2 *__restrict__ part, 
 constexpr int MF_THREADS = 256;
 constexpr int MF_WAVES = 4;
 constexpr int MF_KT = 2;                 // key tiles of 16 per wave iteration (share each B fragment)
-constexpr int MF_MAX_CHUNK = 2048;       // largest key chunk of a workgroup
 constexpr float MF_BIG = 1.0e30f;        // a tile sum above this re-references the row (2^100)
 
 // Arrange the M query rows of KV head h as MFMA B fragments in LDS.

@@ -118,24 +118,42 @@ void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParam
   }
 }
 
-static int32_t pick_chunk(int64_t keys_per_problem, int64_t problems, int32_t lo, int32_t hi) {
-  // Aim for about 2048 workgroups over the whole launch (256 CUs, several resident each),
-  // with power-of-two chunks between lo and hi keys.
-  int64_t total = keys_per_problem * problems;
-  int32_t c = hi;
-  while (c > lo && total / c < 2048) c >>= 1;
-  return c;
+// Number of (row, chunk) work items that hold at least one key, for chunks of `chunk` keys.
+static int64_t count_items(const BatchParams &bp, int32_t B, int64_t rows_per_seq, int32_t drop, int32_t chunk) {
+  int64_t n = 0;
+  for (int32_t b = 0; b < B; ++b) n += ceil_div(std::max(bp.seq[b].L - drop, 0), chunk) * rows_per_seq;
+  return n;
 }
 
-ScorePlan plan_score(const Shape &s, int32_t n_groups) {
+// Keys per workgroup.  The score kernels keep three workgroups resident on each of the 256
+// compute units, and a workgroup's fixed cost (staging the query fragments, the first key
+// load, the epilogue) is several microseconds: the launch is fastest when its non-empty work
+// items fill those 768 slots a whole number of times with chunks as long as the kernels allow.
+// Chunks are multiples of 128 keys (one iteration of a workgroup); `drop` keys at the end of
+// every sequence are not part of the pass.
+static int32_t pick_chunk(const BatchParams &bp, int32_t B, int64_t rows_per_seq, int32_t drop, int32_t lo, int32_t hi) {
+  const int64_t slots = 768;
+  int64_t total = 0;
+  for (int32_t b = 0; b < B; ++b) total += (int64_t)std::max(bp.seq[b].L - drop, 0) * rows_per_seq;
+  if (total <= 0) return lo;
+  for (int64_t rounds = 1; rounds <= 64; ++rounds) {
+    int64_t c = ceil_div(ceil_div(total, slots * rounds), 128) * 128;
+    if (c < lo) return lo;
+    while (c <= hi && count_items(bp, B, rows_per_seq, drop, (int32_t)c) > slots * rounds) c += 128;
+    if (c <= hi) return (int32_t)c;
+  }
+  return hi;
+}
+
+ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   ScorePlan pl;
   pl.m_pad = (s.M + 15) / 16 * 16;
   pl.mfma = (s.dtype == WKV_BF16) && pl.m_pad <= 128;
-  const int64_t problems = (int64_t)s.B * s.Hkv * n_groups;
+  const int64_t rows_per_seq = (int64_t)s.Hkv * n_groups;
   const int32_t Lmax = s.t_stride + s.w_obs;
-  pl.chunk1 = pick_chunk(Lmax, problems, 256, 2048);
+  pl.chunk1 = pick_chunk(bp, s.B, rows_per_seq, 0, 256, MAX_CHUNK1);
   pl.n_chunks1 = (int32_t)ceil_div(Lmax, pl.chunk1);
-  pl.chunk2 = pick_chunk(s.t_stride > 0 ? s.t_stride : 1, problems, 256, 2048);
+  pl.chunk2 = pick_chunk(bp, s.B, rows_per_seq, s.w_obs, 256, MAX_CHUNK2);
   pl.n_chunks2 = (int32_t)ceil_div(s.t_stride > 0 ? s.t_stride : 1, pl.chunk2);
   return pl;
 }
@@ -175,7 +193,7 @@ size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups) {
   if (n_groups < 1 || n_groups > WKV_MAX_GROUPS) { set_error("n_groups outside [1, %d]", WKV_MAX_GROUPS); return 0; }
   Shape s; BatchParams bp;
   fill_shape(problem, dm, &s, &bp);
-  ScorePlan pl = plan_score(s, n_groups);
+  ScorePlan pl = plan_score(s, bp, n_groups);
   return carve_workspace(s, pl, n_groups, nullptr).bytes;
 }
 

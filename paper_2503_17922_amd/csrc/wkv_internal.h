@@ -47,6 +47,11 @@ struct Shape {
 };
 
 // How the score passes split the key axis into workgroup chunks.
+// Longest key chunk of one workgroup: pass 1 keeps nothing per key; pass 2 stages the chunk's
+// token scores in LDS (4 bytes per key).
+constexpr int32_t MAX_CHUNK1 = 8192;
+constexpr int32_t MAX_CHUNK2 = 4096;
+
 struct ScorePlan {
   int32_t chunk1, n_chunks1;   // stats pass
   int32_t chunk2, n_chunks2;   // score pass (over t_stride)
@@ -66,7 +71,7 @@ struct Workspace {
 void set_error(const char *fmt, ...);
 wkv_status validate(const wkv_problem *p, wkv_dims *dims);
 void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParams *bp);
-ScorePlan plan_score(const Shape &s, int32_t n_groups);
+ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups);
 Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base);
 
 // ---- launchers (one per kernel family) ----------------------------------------------------

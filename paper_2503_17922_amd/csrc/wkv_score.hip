@@ -180,7 +180,7 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
 // sums of pass 2 are in-lane adds over the row tiles plus one 16-lane DPP reduction.
 // PASS 1: stats.  PASS 2: scores.
 template <int D, int MT, int PASS>
-__global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
+__global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    const float *__restrict__ lse_g,
                                                                    float *__restrict__ t_out) {
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
   // Pass 2 collects the chunk's token scores here and writes them out once at the end: global
   // stores inside the loop would share the vector-memory counter with the key prefetch and make
   // every wait for keys also wait for store acknowledgements.
-  __shared__ float t_s[PASS == 2 ? MF_MAX_CHUNK : 1];
+  __shared__ float t_s[PASS == 2 ? MAX_CHUNK2 + 256 : 1];
 
   // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
   // are the ones most likely still held by the memory-side cache.
@@ -216,6 +216,11 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
       for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
       return;
     }
+  }
+  if (PASS == 1 && c0 >= L) {                         // a chunk past the end of a short sequence
+    for (int r = threadIdx.x; r < pl.m_pad; r += MF_THREADS)
+      partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(-INFINITY, 0.0f);
+    return;
   }
   stage_q_fragments<D, MT>(s, gp.q[g], b, h, qfrag);
   __syncthreads();
@@ -245,54 +250,71 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
     // Past the end of the chunk the row index clamps to the chunk's last key (a cache hit).
     load_k<KS>(kn, kbase, s.kv_st, j0 + MF_WAVES * STEP, col, cend);
 
-    // ---- logits: acc[n][mt][e] = k_{j0+16n+4*quad+e} . q_{16*mt+col} -----------------------
+    // ---- logits acc[n][mt][e] = k_{j0+16n+4*quad+e} . q_{16*mt+col}, and their exponentials --------
+    // Written so that the MFMAs of row tile mt and the exponentials of row tile mt-1 alternate
+    // in ONE basic block: the matrix pipe and the vector ALU then overlap inside a wave instead
+    // of taking turns (the rare paths - mask, re-reference - come after the block).
     f32x4 acc[MF_KT][MT];
+    float psum[MT];                                     // pass 1: sum of the tile's terms per row
+    f32x4 tq[MF_KT];                                    // pass 2: column sums over this lane's rows
 #pragma unroll
-    for (int n = 0; n < MF_KT; ++n)
+    for (int n = 0; n < MF_KT; ++n) tq[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt <= MT; ++mt) {
+      if (mt < MT) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int ks = 0; ks < KS; ++ks) {
+          const uint4 qraw = qfrag[(mt * KS + ks) * 64 + lane];
+          const bf16x8 qb = *(const bf16x8 *)&qraw;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 qraw = qfrag[(mt * KS + ks) * 64 + lane];
-        const bf16x8 qb = *(const bf16x8 *)&qraw;
-#pragma unroll
-        for (int n = 0; n < MF_KT; ++n)
-          acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.f[n][ks], qb, acc[n][mt], 0, 0, 0);
+          for (int n = 0; n < MF_KT; ++n)
+            acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.f[n][ks], qb,
+                                                                  ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[n][mt], 0, 0, 0);
+        }
       }
+      if (mt > 0) {
+        const int m1 = mt - 1;
+        if (PASS == 1) {
+          float a = 0.0f;
+#pragma unroll
+          for (int n = 0; n < MF_KT; ++n)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a += fast_exp2(fmaf(acc[n][m1][e], c1, -mref[m1]));
+          psum[m1] = a;
+        } else {
+#pragma unroll
+          for (int n = 0; n < MF_KT; ++n)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tq[n][e] += fast_exp2(fmaf(acc[n][m1][e], c1, -lse_r[m1]));
+        }
+      }
+    }
 
     if (PASS == 1) {
       if (j0 + STEP > n_review) {
         // tiles that touch the observation block: causal mask (key j visible to observation
-        // query io iff j <= n_review + io) and the end of the sequence
+        // query io iff j <= n_review + io) and the end of the sequence; redo their sums
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const int r = mt * 16 + col;
           const int last_vis = r < s.M ? n_review + (r % s.w_obs) : -1;
+          float a = 0.0f;
 #pragma unroll
           for (int n = 0; n < MF_KT; ++n)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const int j = j0 + n * 16 + quad * 4 + e;
               if (j > last_vis || j >= cend) acc[n][mt][e] = -INFINITY;
+              a += fast_exp2(fmaf(acc[n][mt][e], c1, -mref[mt]));
             }
+          psum[mt] = a;
         }
       }
-      // z += sum 2^(v - mref).  A sum that is huge, infinite or NaN (first tile: mref = -inf)
-      // means a logit far above the row's reference: re-reference the row and redo the tile.
-      float psum[MT];
+      // A sum that is huge, infinite or NaN (first tile: mref = -inf) means a logit far above the
+      // row's reference: re-reference the row and redo its part of the tile.
       bool redo = false;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        float a = 0.0f;
-#pragma unroll
-        for (int n = 0; n < MF_KT; ++n)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a += fast_exp2(fmaf(acc[n][mt][e], c1, -mref[mt]));
-        psum[mt] = a;
-        redo |= !(a <= MF_BIG);
-      }
+      for (int mt = 0; mt < MT; ++mt) redo |= !(psum[mt] <= MF_BIG);
       if (__any(redo)) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -319,18 +341,15 @@ __global__ __launch_bounds__(MF_THREADS, 2) void score_mfma_kernel(Shape s, Batc
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) zsum[mt] += psum[mt];
     } else {
-      // t_j = sum over this lane's MT rows, then over the 16 lanes (rows 16*mt + 0..15)
+      // t_j: the lane's partial column sums, summed over the 16 lanes (rows 16*mt + 0..15)
+      // Every lane stores (lanes other than the first of each 16 into a scrap area past the
+      // chunk): a store under a lane predicate would put a branch into the middle of the block.
+      float *dst = col == 0 ? t_s + (j0 - c0) + quad * 4 : t_s + MAX_CHUNK2 + lane * 4;
 #pragma unroll
       for (int n = 0; n < MF_KT; ++n) {
-        f32x4 tq;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float a = 0.0f;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) a += fast_exp2(fmaf(acc[n][mt][e], c1, -lse_r[mt]));
-          tq[e] = row16_sum(a);
-        }
-        if (col == 0) *(f32x4 *)(t_s + (j0 - c0) + n * 16 + quad * 4) = tq;   // 4 consecutive keys per quad
+        for (int e = 0; e < 4; ++e) tq[n][e] = row16_sum(tq[n][e]);
+        *(f32x4 *)(dst + (col == 0 ? n * 16 : 0)) = tq[n];                // 4 consecutive keys per quad
       }
     }
   };
