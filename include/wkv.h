@@ -106,13 +106,22 @@ size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups);
  * Eq. 1-2: token scores of one layer group.
  *   q_obs   device, layout above
  *   k_first device, K of the group's first layer
+ *   lse_obs device float32 [batch, n_q_heads, w_obs] (contiguous), or NULL.  The prefill
+ *           attention that produced the cache already holds, for every query row i, the
+ *           normaliser of Eq. 1 as lse_i = ln sum_{j <= pos(i)} exp(scale * q_i . k_j) (natural
+ *           logarithm, causal, over the whole prefix, the same `scale` as here).  When it is
+ *           passed for the w_obs observation rows, A_ij = exp(scale * q_i . k_j - lse_i) is
+ *           evaluated directly and the keys are read once; with NULL the library computes the
+ *           normalisers itself in a first pass over the keys.  A wrong lse_obs gives wrong
+ *           scores; it is not checked.
  *   t_out   device float32 [batch, n_kv_heads, t_stride]; entries j < L_b - w_obs are written,
  *           the rest of each row is set to 0.
  * The softmax runs in fp32 on fp32-accumulated logits; no exponent is taken of an
  * unshifted logit, so any finite inputs are safe.
  */
 wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *k_first,
-                     float *t_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+                     const float *lse_obs, float *t_out, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
 
 /*
  * Eq. 3-4: window scores.
@@ -158,6 +167,8 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
  * The whole path (Eq. 1-4, selection, sharing, gather) for n_groups layer groups of gamma
  * layers each, batched so that every stage is one launch over all groups.
  *   q_obs_groups   host array [n_groups] of device pointers: q_obs of each group's first layer
+ *   lse_obs_groups NULL, or host array [n_groups] of device pointers: lse_obs of each group's
+ *                  first layer as described at wkv_score (all groups or none)
  *   k_layers, v_layers, k_out_layers, v_out_layers
  *                  host arrays [n_groups*gamma] of device pointers, layer l of group g at
  *                  index g*gamma + l; group g is scored on k_layers[g*gamma] only
@@ -168,7 +179,7 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
  * n_groups <= WKV_MAX_GROUPS, n_groups*gamma <= WKV_MAX_LAYERS.
  */
 wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
-                               const void *const *q_obs_groups,
+                               const void *const *q_obs_groups, const float *const *lse_obs_groups,
                                const void *const *k_layers, const void *const *v_layers,
                                void *const *k_out_layers, void *const *v_out_layers,
                                int32_t *win_idx_out, int32_t *tok_idx_out, int32_t *n_keep_out,
@@ -180,13 +191,15 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
  * stream, and reports each kernel's duration.  It creates and destroys HIP events and blocks
  * the calling thread, so it is for benchmarks and profiling, not for serving.
  *   stage_ms_out  host float [WKV_N_STAGES]: milliseconds of, in order, the softmax-statistics
- *                 pass (Eq. 1), the score pass (Eq. 1-2), window pooling (Eq. 3-4; 0 here, because
+ *                 pass (Eq. 1; with lse_obs_groups, the conversion of the given normalisers),
+ *                 the score pass (Eq. 1-2), window pooling (Eq. 3-4; 0 here, because
  *                 this call pools inside the selection kernel), pooling + top-k selection
  *                 (2.2.1) and the shared-index gather (2.2.2).
  */
 #define WKV_N_STAGES 5
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                         const void *const *q_obs_groups,
+                                        const float *const *lse_obs_groups,
                                         const void *const *k_layers, const void *const *v_layers,
                                         void *const *k_out_layers, void *const *v_out_layers,
                                         int32_t *win_idx_out, int32_t *tok_idx_out,

@@ -28,7 +28,8 @@ Parity pins (tests/test_oracle_pins.py): rows of A sum to 1; a hand-built ration
 zero queries (harmonic numbers) and two-level keys (pins the 1/sqrt(d) scale); mass
 conservation; library pooling routines (mean / max_pool1d / topk); exhaustive search over all
 window subsets; a scalar pure-Python re-derivation on tiny inputs; index_select for the
-gather.  The absolute values of t and s on random data have no printed example in the paper:
+gather; scipy's logsumexp and ln(position+1) for the hand-over form of the normaliser.
+The absolute values of t and s on random data have no printed example in the paper:
 beyond those pins they are "parity unpinned".  The value of p in aggregation mode, the
 partial-window rule and the budget rounding are conventions of this repository (the paper
 gives none) and are likewise "parity unpinned".
@@ -65,6 +66,26 @@ def attention_probs(q_obs: np.ndarray, keys: np.ndarray, scale: float | None = N
     logits = logits - logits.max(axis=1, keepdims=True)
     e = np.exp(logits)
     return e / e.sum(axis=1, keepdims=True)
+
+
+def softmax_lse(q_obs: np.ndarray, keys: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """The normaliser of Eq. 1 in the form an attention kernel hands it on: for each observation
+    query i, lse_i = ln sum_{j <= n-alpha+i} exp(q_i . k_j / sqrt(d)), so A_ij = exp(logit_ij - lse_i).
+
+    q_obs: [alpha, d], keys: [n, d]; returns [alpha].
+    """
+    q_obs = np.asarray(q_obs, dtype=np.float64)
+    keys = np.asarray(keys, dtype=np.float64)
+    alpha, d = q_obs.shape
+    n = keys.shape[0]
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty(alpha, dtype=np.float64)
+    for i in range(alpha):
+        logits = (keys[: n - alpha + i + 1] @ q_obs[i]) * scale    # the keys this query may see
+        m = logits.max()
+        out[i] = m + math.log(np.exp(logits - m).sum())
+    return out
 
 
 # --------------------------------------------------------------------------------------

@@ -65,13 +65,13 @@ def lib() -> C.CDLL:
     P, VP = C.POINTER(_Problem), C.c_void_p
     l.wkv_get_dims.argtypes = [P, C.POINTER(Dims)]; l.wkv_get_dims.restype = C.c_int
     l.wkv_workspace_bytes.argtypes = [P, C.c_int32]; l.wkv_workspace_bytes.restype = C.c_size_t
-    l.wkv_score.argtypes = [P, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_score.restype = C.c_int
+    l.wkv_score.argtypes = [P, VP, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_score.restype = C.c_int
     l.wkv_window_pool.argtypes = [P, VP, VP, VP]; l.wkv_window_pool.restype = C.c_int
     l.wkv_topk_windows.argtypes = [P, VP, VP, VP, VP, VP]; l.wkv_topk_windows.restype = C.c_int
     l.wkv_gather_group.argtypes = [P, C.c_int32, C.POINTER(VP), C.POINTER(VP), VP, VP,
                                    C.POINTER(VP), C.POINTER(VP), VP]
     l.wkv_gather_group.restype = C.c_int
-    l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
+    l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
                                       C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP, C.c_size_t, VP]
     l.wkv_compress_groups.restype = C.c_int
     l.wkv_compress_groups_profiled.argtypes = l.wkv_compress_groups.argtypes + [C.POINTER(C.c_float)]
@@ -150,9 +150,10 @@ def wkv_workspace_bytes(problem: Problem, n_groups: int = 1) -> int:
     return int(n)
 
 
-def wkv_score(problem, q_obs, k_first, t_out, workspace, stream=None) -> None:
+def wkv_score(problem, q_obs, k_first, lse_obs, t_out, workspace, stream=None) -> None:
+    """``lse_obs``: float32 [batch, n_q_heads, w_obs] natural-log softmax normalisers, or None."""
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().wkv_score(problem.ref(), _ptr(q_obs), _ptr(k_first), _ptr(t_out), _ptr(workspace),
+    _check(lib().wkv_score(problem.ref(), _ptr(q_obs), _ptr(k_first), _ptr(lse_obs), _ptr(t_out), _ptr(workspace),
                            ws_bytes, _stream(stream)))
 
 
@@ -177,12 +178,13 @@ class CompressCall:
     """``wkv_compress_groups`` with its host pointer arrays marshalled once, for callers that
     repeat the same call (the benchmark's timed loop)."""
 
-    def __init__(self, problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers,
+    def __init__(self, problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
                  v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace):
-        self._keep = (problem, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
+        self._keep = (problem, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
                       win_idx_out, tok_idx_out, n_keep_out, workspace)
         ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-        self._args = (problem.ref(), n_groups, gamma, _ptr_array(q_obs_groups), _ptr_array(k_layers),
+        lse_arr = _ptr_array(lse_obs_groups) if lse_obs_groups is not None else None
+        self._args = (problem.ref(), n_groups, gamma, _ptr_array(q_obs_groups), lse_arr, _ptr_array(k_layers),
                       _ptr_array(v_layers), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
                       _ptr(win_idx_out), _ptr(tok_idx_out), _ptr(n_keep_out), _ptr(workspace), ws_bytes)
         self._fn = lib().wkv_compress_groups
@@ -198,10 +200,10 @@ class CompressCall:
         return list(ms)
 
 
-def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers,
+def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
                         v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, stream=None) -> None:
-    CompressCall(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
-                 win_idx_out, tok_idx_out, n_keep_out, workspace)(stream)
+    CompressCall(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
+                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace)(stream)
 
 
 def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:

@@ -44,21 +44,23 @@ wkv_status check_workspace(const Shape &s, const ScorePlan &pl, int32_t n_groups
 
 extern "C" {
 
-wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *k_first, float *t_out,
-                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *k_first, const float *lse_obs,
+                     float *t_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
   Prepared pr;
   wkv_status st = prepare(problem, &pr);
   if (st != WKV_OK) return st;
   if (!q_obs || !k_first || !t_out) { set_error("q_obs / k_first / t_out is NULL"); return WKV_ERR_INVALID_ARG; }
   if (misaligned(q_obs, 16) || misaligned(k_first, 16)) { set_error("q_obs and k_first must be 16-byte aligned"); return WKV_ERR_INVALID_ARG; }
+  if (misaligned(lse_obs, 4)) { set_error("lse_obs must be 4-byte aligned"); return WKV_ERR_INVALID_ARG; }
   const ScorePlan pl = plan_score(pr.shape, pr.bp, 1);
   Workspace ws;
   st = check_workspace(pr.shape, pl, 1, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;
   GroupPtrs gp;
   std::memset(&gp, 0, sizeof(gp));
-  gp.q[0] = q_obs; gp.k[0] = k_first;
-  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, ws.partials, ws.lse, t_out, (hipStream_t)hip_stream);
+  gp.q[0] = q_obs; gp.k[0] = k_first; gp.lse[0] = lse_obs;
+  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, lse_obs != nullptr, ws.partials, ws.lse, t_out,
+                              (hipStream_t)hip_stream);
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_score launch");
 }
 
@@ -120,7 +122,8 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers, const 
 }
 
 static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
-                                const void *const *q_obs_groups, const void *const *k_layers,
+                                const void *const *q_obs_groups, const float *const *lse_obs_groups,
+                                const void *const *k_layers,
                                 const void *const *v_layers, void *const *k_out_layers,
                                 void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                 int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream,
@@ -147,6 +150,13 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
     }
     gp.q[g] = q_obs_groups[g];
     gp.k[g] = k_layers[(size_t)g * gamma];     // Section 2.2.2: the group's first layer is scored
+    if (lse_obs_groups) {
+      if (!lse_obs_groups[g] || misaligned(lse_obs_groups[g], 4)) {
+        set_error("lse_obs_groups[%d] is NULL or not 4-byte aligned (pass a NULL array to have the statistics computed)", g);
+        return WKV_ERR_INVALID_ARG;
+      }
+      gp.lse[g] = lse_obs_groups[g];
+    }
   }
   const ScorePlan pl = plan_score(pr.shape, pr.bp, n_groups);
   Workspace ws;
@@ -156,7 +166,8 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
   hipError_t e;
 #define WKV_MARK(i) if (ev && (e = hipEventRecord(ev[i], stream)) != hipSuccess) return hip_fail(e, "event record");
   WKV_MARK(0)
-  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, ws.partials, ws.lse, ws.t, stream, ev ? ev[1] : nullptr);
+  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, lse_obs_groups != nullptr, ws.partials, ws.lse, ws.t, stream,
+                   ev ? ev[1] : nullptr);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
   WKV_MARK(3)     // pooling runs inside the selection kernel here: its own slot stays empty
@@ -171,16 +182,19 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
 }
 
 wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
-                               const void *const *q_obs_groups, const void *const *k_layers,
+                               const void *const *q_obs_groups, const float *const *lse_obs_groups,
+                               const void *const *k_layers,
                                const void *const *v_layers, void *const *k_out_layers,
                                void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return compress_impl(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
-                       win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, nullptr);
+  return compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
+                       v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream,
+                       nullptr);
 }
 
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
-                                        const void *const *q_obs_groups, const void *const *k_layers,
+                                        const void *const *q_obs_groups, const float *const *lse_obs_groups,
+                                        const void *const *k_layers,
                                         const void *const *v_layers, void *const *k_out_layers,
                                         void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                         int32_t *n_keep_out, void *workspace, size_t workspace_bytes,
@@ -195,8 +209,8 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
   if (e != hipSuccess) {
     st = hip_fail(e, "hipEventCreate");
   } else {
-    st = compress_impl(problem, n_groups, gamma, q_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
-                       win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, ev);
+    st = compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
+                       v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, ev);
     if (st == WKV_OK) {
       if ((e = hipEventSynchronize(ev[WKV_N_STAGES])) != hipSuccess) st = hip_fail(e, "hipEventSynchronize");
       for (int i = 0; st == WKV_OK && i < WKV_N_STAGES; ++i)

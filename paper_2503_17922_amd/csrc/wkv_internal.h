@@ -24,6 +24,7 @@ struct BatchParams {
 struct GroupPtrs {
   const void *q[WKV_MAX_GROUPS];
   const void *k[WKV_MAX_GROUPS];
+  const float *lse[WKV_MAX_GROUPS];   // caller's softmax log-sum-exp of the observation rows, or all null
 };
 
 // Per-layer device pointers for the gather.
@@ -78,8 +79,8 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_group
 // All return hipSuccess or the launch error. Pointers are device pointers unless noted.
 // `mid`, if not null, is recorded between the stats pass and the score pass.
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &plan,
-                        const GroupPtrs &gp, int32_t n_groups, float2 *partials, float *lse, float *t_out,
-                        hipStream_t stream, hipEvent_t mid = nullptr);
+                        const GroupPtrs &gp, int32_t n_groups, bool have_lse, float2 *partials, float *lse,
+                        float *t_out, hipStream_t stream, hipEvent_t mid = nullptr);
 hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
                        float *s_out, hipStream_t stream);
 hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,

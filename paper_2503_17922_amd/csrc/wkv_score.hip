@@ -13,6 +13,9 @@
 //   fold            one tiny launch turns the partials of every row into lse2_i = m_i + log2(z_i).
 //   pass 2 (score)  each workgroup recomputes its logits and writes t_j = sum_i 2^(v_ij - lse2_i).
 //
+// A caller whose prefill attention kept the normalisers of the observation rows hands them
+// over; pass 1 and the fold are then skipped and the keys are read once.
+//
 // Two kernel families implement the passes:
 //   * MFMA (bf16 inputs, M <= 128): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
 //     loaded straight from global memory into registers in operand layout, so K never passes
@@ -57,6 +60,18 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(Shape s, ScorePlan p
       lse[row * pl.m_pad + r] = r < s.M ? m + fast_log2(z) : INFINITY;   // padded rows: 2^-inf = 0
     }
   }
+}
+
+// The base-2 log-sum-exp of softmax row r of (group g, sequence b, KV head h): converted from the
+// caller's natural-log normalisers [B, Hq, w_obs] when they were handed over (the rows of a KV
+// head are contiguous there), else what the fold left in the workspace.  Padded rows get +inf
+// (2^-inf = 0: they contribute nothing).
+__device__ __forceinline__ float row_lse2(const Shape &s, const ScorePlan &pl, const GroupPtrs &gp,
+                                          const float *__restrict__ lse_ws, int g, int b, int h, int64_t row, int r) {
+  if (r >= s.M) return INFINITY;
+  const float *given = gp.lse[g];
+  if (given) return given[((int64_t)b * s.Hq + (int64_t)h * s.G) * s.w_obs + r] * 1.4426950408889634f;
+  return lse_ws[row * pl.m_pad + r];
 }
 
 // =========================================================================================
@@ -147,7 +162,7 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
     const int hq = h * s.G + r / s.w_obs, io = r % s.w_obs;
     qs[i] = Elem<T>::load(gp.q[g], (int64_t)b * s.q_sb + (int64_t)hq * s.q_sh + (int64_t)io * s.q_st + c);
   }
-  for (int r = threadIdx.x; r < s.M; r += GEN_THREADS) lse[r] = lse_g[row * pl.m_pad + r];
+  for (int r = threadIdx.x; r < s.M; r += GEN_THREADS) lse[r] = row_lse2(s, pl, gp, lse_g, g, b, h, row, r);
   __syncthreads();
   const int64_t koff = (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh;
   for (int j = c0 + threadIdx.x; j < cend; j += GEN_THREADS) {
@@ -229,7 +244,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   float lse_r[MT], mref[MT], zsum[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    lse_r[mt] = PASS == 2 ? lse_g[row * pl.m_pad + min(mt * 16 + col, pl.m_pad - 1)] : 0.0f;
+    lse_r[mt] = PASS == 2 ? row_lse2(s, pl, gp, lse_g, g, b, h, row, mt * 16 + col) : 0.0f;
     mref[mt] = -INFINITY;
     zsum[mt] = 0.0f;
   }
@@ -396,17 +411,22 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
 // =========================================================================================
 template <int D, int MT>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                              int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
-                              hipEvent_t mid) {
+                              int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
+                              hipStream_t stream, hipEvent_t mid) {
   dim3 block(MF_THREADS);
-  dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
-  if (s.t_stride <= 0) return hipSuccess;
-  hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e;
+  if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
+    if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
+    if (s.t_stride <= 0) return hipSuccess;
+  } else {
+    dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
+    if (s.t_stride <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
   return hipGetLastError();
@@ -414,19 +434,24 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
 
 template <typename T, int D>
 static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                                 int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
-                                 hipEvent_t mid) {
+                                 int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
+                                 hipStream_t stream, hipEvent_t mid) {
   int R = 1;
   while (R < pl.m_pad) R <<= 1;
   dim3 block(GEN_THREADS);
-  dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((stats_generic_kernel<T, D>), g1, block, 0, stream, s, bp, gp, pl, partials, R);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
-  if (s.t_stride <= 0) return hipSuccess;
-  hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e;
+  if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
+    if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
+    if (s.t_stride <= 0) return hipSuccess;
+  } else {
+    dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
+    hipLaunchKernelGGL((stats_generic_kernel<T, D>), g1, block, 0, stream, s, bp, gp, pl, partials, R);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
+    if (s.t_stride <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   const size_t lds = ((size_t)s.M * D + s.M) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
@@ -441,23 +466,23 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
 }
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                        int32_t n_groups, float2 *partials, float *lse, float *t_out, hipStream_t stream,
-                        hipEvent_t mid) {
+                        int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
+                        hipStream_t stream, hipEvent_t mid) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
 #define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
+  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
     WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
     WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
 #undef WKV_MFMA_CASE
     return hipErrorInvalidValue;
   }
   if (s.dtype == WKV_BF16) {
-    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
-    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
+    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
+    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
   }
-  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
-  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, partials, lse, t_out, stream, mid);
+  if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
+  return launch_generic<float, 64>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
 }
 
 }  // namespace wkv

@@ -51,13 +51,27 @@ class DeviceState:
         self.ws_bytes = W.wkv_workspace_bytes(self.problem, G)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
-    def compress(self):
+    def compress(self, lse=None):
+        """``lse``: None, or one float32 [B, Hq, w_obs] device tensor per group (normaliser hand-over)."""
         w = self.w
-        W.wkv_compress_groups(self.problem, w.n_groups, w.gamma, self.q, self.k, self.v, self.k_out, self.v_out,
+        W.wkv_compress_groups(self.problem, w.n_groups, w.gamma, self.q, lse, self.k, self.v, self.k_out, self.v_out,
                               self.win_idx, self.tok_idx, self.n_keep, self.workspace)
         torch.cuda.synchronize()
 
-    def stages(self, g: int):
+    def oracle_lse(self, g: int) -> torch.Tensor:
+        """The oracle's ln-sum-exp of every observation row of group g, as the float32 device tensor
+        [B, Hq, w_obs] a prefill attention kernel would hand over."""
+        w = self.w
+        G = w.q_per_kv
+        out = np.zeros((w.batch, w.n_q_heads, w.w_obs), dtype=np.float64)
+        for b in range(w.batch):
+            for h in range(w.n_kv_heads):
+                k = host_f64(w, self.k[g * w.gamma][b, h, : w.seq_len[b]])
+                for gq in range(G):
+                    out[b, h * G + gq] = O.softmax_lse(host_f64(w, self.q[g][b, h * G + gq]), k)
+        return torch.from_numpy(out.astype(np.float32)).to(self.device)
+
+    def stages(self, g: int, lse=None):
         """The four stage calls on group g; returns (t, s, win_idx, tok_idx, n_keep) tensors."""
         w, d = self.w, self.dims
         B, H = w.batch, w.n_kv_heads
@@ -68,7 +82,7 @@ class DeviceState:
         ti = torch.full((B, H, d.nkeep_max), -7, dtype=torch.int32, device=dev)
         nk = torch.full((B, H), -7, dtype=torch.int32, device=dev)
         ws = torch.empty(W.wkv_workspace_bytes(self.problem, 1), dtype=torch.uint8, device=dev)
-        W.wkv_score(self.problem, self.q[g], self.k[g * w.gamma], t, ws)
+        W.wkv_score(self.problem, self.q[g], self.k[g * w.gamma], lse, t, ws)
         W.wkv_window_pool(self.problem, t, s)
         W.wkv_topk_windows(self.problem, s, wi, ti, nk)
         torch.cuda.synchronize()

@@ -83,21 +83,22 @@ def test_stage_calls_validate_before_any_launch():
     lib = W.lib()
     p = _problem()
     null = C.c_void_p(0)
-    assert lib.wkv_score(p.ref(), null, null, null, null, 0, null) == W.WKV_ERR_INVALID_ARG
+    assert lib.wkv_score(p.ref(), null, null, null, null, null, 0, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_window_pool(p.ref(), null, null, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_topk_windows(p.ref(), null, null, null, null, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_gather_group(p.ref(), 1, None, None, null, null, None, None, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_get_dims(None, None) == W.WKV_ERR_INVALID_ARG
     fake = C.c_void_p(4096)      # aligned, non-null, never dereferenced on these paths
-    assert lib.wkv_score(p.ref(), fake, fake, fake, null, 0, null) == W.WKV_ERR_WORKSPACE
-    assert lib.wkv_score(p.ref(), fake, fake, fake, C.c_void_p(4096 + 64), 1 << 30, null) == W.WKV_ERR_WORKSPACE
-    assert lib.wkv_score(p.ref(), fake, fake, fake, fake, 16, null) == W.WKV_ERR_WORKSPACE
+    assert lib.wkv_score(p.ref(), fake, fake, null, fake, null, 0, null) == W.WKV_ERR_WORKSPACE
+    assert lib.wkv_score(p.ref(), fake, fake, null, fake, C.c_void_p(4096 + 64), 1 << 30, null) == W.WKV_ERR_WORKSPACE
+    assert lib.wkv_score(p.ref(), fake, fake, fake, fake, fake, 16, null) == W.WKV_ERR_WORKSPACE
     assert b"needed" in lib.wkv_last_error()
-    assert lib.wkv_score(p.ref(), C.c_void_p(4100), fake, fake, fake, 1 << 30, null) == W.WKV_ERR_INVALID_ARG
+    assert lib.wkv_score(p.ref(), C.c_void_p(4100), fake, null, fake, fake, 1 << 30, null) == W.WKV_ERR_INVALID_ARG
+    assert lib.wkv_score(p.ref(), fake, fake, C.c_void_p(4098), fake, fake, 1 << 30, null) == W.WKV_ERR_INVALID_ARG
     arr = (C.c_void_p * 1)(4096)
     assert lib.wkv_gather_group(p.ref(), 0, arr, arr, fake, fake, arr, arr, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_gather_group(p.ref(), 65, arr, arr, fake, fake, arr, arr, null) == W.WKV_ERR_INVALID_ARG
-    assert lib.wkv_compress_groups(p.ref(), 8, 9, arr, arr, arr, arr, arr, fake, fake, fake, fake, 1 << 30,
+    assert lib.wkv_compress_groups(p.ref(), 8, 9, arr, None, arr, arr, arr, arr, fake, fake, fake, fake, 1 << 30,
                                    null) == W.WKV_ERR_INVALID_ARG
 
 

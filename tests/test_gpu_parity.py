@@ -192,11 +192,70 @@ def test_strided_layout(device):
     ko = [torch.full((B, nk, H, d), 5.0, dtype=k.dtype, device=device) for k in st.k]
     vo = [torch.full((B, nk, H, d), 5.0, dtype=k.dtype, device=device) for k in st.k]
     wi, ti, nkp = torch.empty_like(st.win_idx), torch.empty_like(st.tok_idx), torch.empty_like(st.n_keep)
-    W.wkv_compress_groups(prob, 1, 2, q2, k2, v2, ko, vo, wi, ti, nkp, st.workspace)
+    W.wkv_compress_groups(prob, 1, 2, q2, None, k2, v2, ko, vo, wi, ti, nkp, st.workspace)
     torch.cuda.synchronize()
     assert torch.equal(wi, st.win_idx) and torch.equal(ti, st.tok_idx) and torch.equal(nkp, st.n_keep)
     for l in range(2):
         assert torch.equal(ko[l].permute(0, 2, 1, 3), st.k_out[l]) and torch.equal(vo[l].permute(0, 2, 1, 3), st.v_out[l])
+
+
+def _check_lse_handoff(w, device, groups_oracle):
+    """With the oracle's normalisers handed over, the score stage must meet the same bar as the
+    two-pass path, and the batched call must pick what the two-pass call picks (up to near-ties)."""
+    st = P.DeviceState(w, device)
+    st.compress()
+    base_win = st.win_idx.cpu().numpy()[..., : st.dims.k_max].copy()
+    lse = [st.oracle_lse(g) if g in groups_oracle else None for g in range(w.n_groups)]
+    B, H = w.batch, w.n_kv_heads
+    for g in groups_oracle:
+        t_dev, s_dev, wi, ti, nk = st.stages(g, lse=lse[g])
+        t_two, _, wi_two, _, _ = st.stages(g)
+        t_host = t_dev.cpu().numpy().astype(np.float64)
+        for b, h in itertools.product(range(B), range(H)):
+            t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
+            n_rev = w.seq_len[b] - w.w_obs
+            P.assert_scores_close(t_host[b, h, :n_rev], t, f"{w.name} lse hand-over g{g} b{b} h{h} t")
+            assert np.all(t_host[b, h, n_rev: st.dims.t_stride] == 0.0)
+            got = wi.cpu().numpy()[b, h, : w.k_windows[b]]
+            P.check_selection(s, sel, got, w.k_windows[b], f"{w.name} lse hand-over g{g} b{b} h{h}")
+        # against the library's own two-pass scores: same values to fp32 rounding of the normaliser
+        np.testing.assert_allclose(t_dev.cpu().numpy(), t_two.cpu().numpy(), rtol=2e-4, atol=1e-12)
+    if len(groups_oracle) == w.n_groups:
+        st.win_idx.fill_(-7); st.tok_idx.fill_(-7); st.n_keep.fill_(-7)
+        for o in st.k_out + st.v_out:
+            o.fill_(7.0)
+        st.compress(lse=lse)
+        win = st.win_idx.cpu().numpy()[..., : st.dims.k_max]
+        tok = st.tok_idx.cpu().numpy(); nkeep = st.n_keep.cpu().numpy()
+        differ = 0
+        for g, b, h in itertools.product(range(w.n_groups), range(B), range(H)):
+            P.check_indices_structure(w, b, win[g, b, h], tok[g, b, h], int(nkeep[g, b, h]), st.dims.k_max,
+                                      st.dims.nkeep_max, f"{w.name} batched lse g{g} b{b} h{h}")
+            t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
+            P.check_selection(s, sel, win[g, b, h, : w.k_windows[b]], w.k_windows[b], f"{w.name} batched lse g{g} b{b} h{h}")
+            differ += not np.array_equal(win[g, b, h], base_win[g, b, h])
+            n = int(nkeep[g, b, h])
+            rows = torch.from_numpy(tok[g, b, h, :n].astype(np.int64)).to(device)
+            for l in range(w.gamma):
+                layer = g * w.gamma + l
+                assert torch.equal(st.k_out[layer][b, h, :n], st.k[layer][b, h].index_select(0, rows))
+                assert torch.equal(st.v_out[layer][b, h, :n], st.v[layer][b, h].index_select(0, rows))
+        print(f"[{w.name}] lse hand-over: {differ} index rows differ from the two-pass call (near-ties only)", flush=True)
+
+
+def test_lse_handoff_small_configs(device):
+    _check_lse_handoff(S.make_workload("c1"), device, groups_oracle=[0])          # fp32, generic kernels
+    _check_lse_handoff(S.make_workload("c2"), device, groups_oracle=[0])          # bf16, MFMA kernels, outlier channels
+    w = _mini(seq_len=[777, 130, 2049], win=[8, 16, 32], top_p=[8, 5, 16], k_windows=[20, 3, 11], n_groups=2, gamma=2)
+    _check_lse_handoff(w, device, groups_oracle=[0, 1])                           # ragged batch, two groups
+
+
+def test_lse_handoff_rejects_partial_arrays(device):
+    w = _mini(seq_len=[300], n_groups=2, gamma=1)
+    st = P.DeviceState(w, device)
+    with pytest.raises(W.WkvError) as e:
+        st.compress(lse=[st.oracle_lse(0), None])
+    assert e.value.status == W.WKV_ERR_INVALID_ARG
 
 
 def test_other_layers_do_not_influence_indices(device):

@@ -135,6 +135,32 @@ def test_matches_torch_sdpa_with_identity_values():
     np.testing.assert_allclose(O.attention_probs(q, K), A_lib, rtol=1e-11, atol=1e-15)
 
 
+def test_lse_matches_scipy_logsumexp_and_recovers_probs():
+    # the hand-over form of the normaliser: a library log-sum-exp over the visible keys, and
+    # exp(logit - lse) must be the probability of Eq. 1
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(11)
+    n, alpha, d = 53, 6, 8
+    q = rng.standard_normal((alpha, d)) * 3.0
+    k = rng.standard_normal((n, d)) * 3.0
+    lse = O.softmax_lse(q, k)
+    A = O.attention_probs(q, k)
+    for i in range(alpha):
+        vis = n - alpha + i + 1
+        logits = (k[:vis] @ q[i]) / math.sqrt(d)
+        assert lse[i] == pytest.approx(logsumexp(logits), rel=1e-13)
+        np.testing.assert_allclose(np.exp(logits - lse[i]), A[i, :vis], rtol=1e-12)
+    # explicit scale
+    np.testing.assert_allclose(O.softmax_lse(q, k, scale=0.5), O.softmax_lse(q * 0.5 * math.sqrt(d), k), rtol=1e-13)
+
+
+def test_lse_of_zero_queries_is_log_of_visible_count():
+    n, alpha, d = 40, 5, 4
+    k = np.random.default_rng(3).standard_normal((n, d))
+    lse = O.softmax_lse(np.zeros((alpha, d)), k)
+    np.testing.assert_allclose(lse, np.log(n - alpha + 1 + np.arange(alpha)), rtol=1e-14)
+
+
 def test_scalar_rederivation_tiny():
     # brute force with scalar loops and math.exp, written term by term from Eq. 1-2.
     r = _rng(5)
