@@ -169,6 +169,11 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
  *   q_obs_groups   host array [n_groups] of device pointers: q_obs of each group's first layer
  *   lse_obs_groups NULL, or host array [n_groups] of device pointers: lse_obs of each group's
  *                  first layer as described at wkv_score (all groups or none)
+ *   k_windows_groups  NULL, or host int32 [n_groups, batch]: windows to keep for sequence b in
+ *                  group g when the groups have budgets of their own (Section 2.2.3, Eq. 5-7;
+ *                  see wkv_group_budgets), 0 <= k <= problem->k_windows[b].  problem->k_windows
+ *                  then only sizes the outputs (k_max, nkeep_max); rows are padded as usual.
+ *                  Needs n_groups*batch <= 1024.  With NULL every group keeps k_windows[b].
  *   k_layers, v_layers, k_out_layers, v_out_layers
  *                  host arrays [n_groups*gamma] of device pointers, layer l of group g at
  *                  index g*gamma + l; group g is scored on k_layers[g*gamma] only
@@ -180,6 +185,7 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
  */
 wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                const void *const *q_obs_groups, const float *const *lse_obs_groups,
+                               const int32_t *k_windows_groups,
                                const void *const *k_layers, const void *const *v_layers,
                                void *const *k_out_layers, void *const *v_out_layers,
                                int32_t *win_idx_out, int32_t *tok_idx_out, int32_t *n_keep_out,
@@ -200,6 +206,7 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                         const void *const *q_obs_groups,
                                         const float *const *lse_obs_groups,
+                                        const int32_t *k_windows_groups,
                                         const void *const *k_layers, const void *const *v_layers,
                                         void *const *k_out_layers, void *const *v_out_layers,
                                         int32_t *win_idx_out, int32_t *tok_idx_out,

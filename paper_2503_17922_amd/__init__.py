@@ -71,8 +71,9 @@ def lib() -> C.CDLL:
     l.wkv_gather_group.argtypes = [P, C.c_int32, C.POINTER(VP), C.POINTER(VP), VP, VP,
                                    C.POINTER(VP), C.POINTER(VP), VP]
     l.wkv_gather_group.restype = C.c_int
-    l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
-                                      C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP, C.c_size_t, VP]
+    l.wkv_compress_groups.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(VP), C.POINTER(VP), C.POINTER(C.c_int32),
+                                      C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP,
+                                      C.c_size_t, VP]
     l.wkv_compress_groups.restype = C.c_int
     l.wkv_compress_groups_profiled.argtypes = l.wkv_compress_groups.argtypes + [C.POINTER(C.c_float)]
     l.wkv_compress_groups_profiled.restype = C.c_int
@@ -179,12 +180,15 @@ class CompressCall:
     repeat the same call (the benchmark's timed loop)."""
 
     def __init__(self, problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
-                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace):
+                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, k_windows_groups=None):
         self._keep = (problem, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers, v_out_layers,
                       win_idx_out, tok_idx_out, n_keep_out, workspace)
         ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
         lse_arr = _ptr_array(lse_obs_groups) if lse_obs_groups is not None else None
-        self._args = (problem.ref(), n_groups, gamma, _ptr_array(q_obs_groups), lse_arr, _ptr_array(k_layers),
+        kg_arr = None
+        if k_windows_groups is not None:       # [n_groups][batch] nested sequence, row-major as the ABI wants
+            kg_arr = _i32([k for row in k_windows_groups for k in row])
+        self._args = (problem.ref(), n_groups, gamma, _ptr_array(q_obs_groups), lse_arr, kg_arr, _ptr_array(k_layers),
                       _ptr_array(v_layers), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
                       _ptr(win_idx_out), _ptr(tok_idx_out), _ptr(n_keep_out), _ptr(workspace), ws_bytes)
         self._fn = lib().wkv_compress_groups
@@ -201,9 +205,12 @@ class CompressCall:
 
 
 def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
-                        v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, stream=None) -> None:
+                        v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, stream=None,
+                        k_windows_groups=None) -> None:
+    """The C entry point's ``k_windows_groups`` (between ``lse_obs_groups`` and ``k_layers`` there)
+    is the trailing keyword here: a nested [n_groups][batch] sequence of ints, or None."""
     CompressCall(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
-                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace)(stream)
+                 v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, k_windows_groups)(stream)
 
 
 def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:

@@ -123,7 +123,7 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers, const 
 
 static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                 const void *const *q_obs_groups, const float *const *lse_obs_groups,
-                                const void *const *k_layers,
+                                const int32_t *k_windows_groups, const void *const *k_layers,
                                 const void *const *v_layers, void *const *k_out_layers,
                                 void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                 int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream,
@@ -158,6 +158,24 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
       gp.lse[g] = lse_obs_groups[g];
     }
   }
+  GroupK gk;
+  std::memset(&gk, 0, sizeof(gk));
+  if (k_windows_groups) {
+    // Section 2.2.3: groups with budgets of their own; problem->k_windows is then the capacity
+    if ((int64_t)n_groups * problem->batch > MAX_GROUP_K) {
+      set_error("per-group budgets support n_groups*batch <= %d", MAX_GROUP_K); return WKV_ERR_UNSUPPORTED;
+    }
+    gk.in_use = 1;
+    for (int32_t g = 0; g < n_groups; ++g)
+      for (int32_t b = 0; b < problem->batch; ++b) {
+        const int32_t kgb = k_windows_groups[(size_t)g * problem->batch + b];
+        if (kgb < 0 || kgb > problem->k_windows[b]) {
+          set_error("k_windows_groups[%d][%d] = %d outside [0, k_windows[%d] = %d]", g, b, kgb, b, problem->k_windows[b]);
+          return WKV_ERR_INVALID_ARG;
+        }
+        gk.k[(size_t)g * problem->batch + b] = (uint16_t)kgb;
+      }
+  }
   const ScorePlan pl = plan_score(pr.shape, pr.bp, n_groups);
   Workspace ws;
   st = check_workspace(pr.shape, pl, n_groups, workspace, workspace_bytes, &ws);
@@ -171,7 +189,7 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
   WKV_MARK(3)     // pooling runs inside the selection kernel here: its own slot stays empty
-  e = launch_select(pr.shape, pr.bp, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
+  e = launch_select(pr.shape, pr.bp, gk, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "select launch");
   WKV_MARK(4)
   e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);
@@ -183,18 +201,18 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
 
 wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                const void *const *q_obs_groups, const float *const *lse_obs_groups,
-                               const void *const *k_layers,
+                               const int32_t *k_windows_groups, const void *const *k_layers,
                                const void *const *v_layers, void *const *k_out_layers,
                                void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
+  return compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_windows_groups, k_layers, v_layers, k_out_layers,
                        v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream,
                        nullptr);
 }
 
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                         const void *const *q_obs_groups, const float *const *lse_obs_groups,
-                                        const void *const *k_layers,
+                                        const int32_t *k_windows_groups, const void *const *k_layers,
                                         const void *const *v_layers, void *const *k_out_layers,
                                         void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
                                         int32_t *n_keep_out, void *workspace, size_t workspace_bytes,
@@ -209,7 +227,7 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
   if (e != hipSuccess) {
     st = hip_fail(e, "hipEventCreate");
   } else {
-    st = compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
+    st = compress_impl(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_windows_groups, k_layers, v_layers, k_out_layers,
                        v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes, hip_stream, ev);
     if (st == WKV_OK) {
       if ((e = hipEventSynchronize(ev[WKV_N_STAGES])) != hipSuccess) st = hip_fail(e, "hipEventSynchronize");

@@ -20,6 +20,14 @@ struct BatchParams {
   SeqParam seq[WKV_MAX_BATCH];
 };
 
+// Windows to keep per (group, sequence) when the groups have budgets of their own (Section
+// 2.2.3); index g * B + b.  Not in use: every group keeps SeqParam::k windows.
+constexpr int32_t MAX_GROUP_K = 1024;
+struct GroupK {
+  int32_t in_use;
+  uint16_t k[MAX_GROUP_K];
+};
+
 // Per-group device pointers of the scored layer.
 struct GroupPtrs {
   const void *q[WKV_MAX_GROUPS];
@@ -86,7 +94,7 @@ hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, 
 hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
                        int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream);
 // Pooling and selection in one launch (same results as launch_pool followed by launch_topk).
-hipError_t launch_select(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
+hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *t,
                          int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream);
 hipError_t launch_gather(const Shape &s, const LayerPtrs &lp, int32_t n_layers, int32_t gamma,
                          const int32_t *tok_idx, const int32_t *n_keep, hipStream_t stream);

@@ -321,13 +321,15 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams
 
 // Pooling and selection in one launch (the path wkv_compress_groups takes): the window scores
 // go straight from registers into the LDS key array and never touch global memory.
-__global__ __launch_bounds__(TOPK_THREADS) void select_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
+__global__ __launch_bounds__(TOPK_THREADS) void select_kernel(Shape s, BatchParams bp, GroupK gk,
+                                                              const float *__restrict__ t,
                                                               int32_t *__restrict__ win_idx,
                                                               int32_t *__restrict__ tok_idx,
                                                               int32_t *__restrict__ n_keep) {
   extern __shared__ uint32_t keys[];
   const int bh = blockIdx.x, b = bh / s.Hkv, g = blockIdx.y;
-  const SeqParam sp = bp.seq[b];
+  SeqParam sp = bp.seq[b];
+  if (gk.in_use) sp.k = gk.k[g * s.B + b];      // the group's own budget
   const int n_review = sp.L - s.w_obs;
   const int nw = (n_review + sp.win - 1) / sp.win;
   const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
@@ -352,7 +354,7 @@ hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, 
   return hipGetLastError();
 }
 
-hipError_t launch_select(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
+hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *t,
                          int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
   const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
   static bool attr_set = false;
@@ -363,7 +365,7 @@ hipError_t launch_select(const Shape &s, const BatchParams &bp, int32_t n_groups
     attr_set = true;
   }
   dim3 grid(s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL(select_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, t, win_idx, tok_idx, n_keep);
+  hipLaunchKernelGGL(select_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, gk, t, win_idx, tok_idx, n_keep);
   return hipGetLastError();
 }
 

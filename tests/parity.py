@@ -51,11 +51,12 @@ class DeviceState:
         self.ws_bytes = W.wkv_workspace_bytes(self.problem, G)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
-    def compress(self, lse=None):
-        """``lse``: None, or one float32 [B, Hq, w_obs] device tensor per group (normaliser hand-over)."""
+    def compress(self, lse=None, k_groups=None):
+        """``lse``: None, or one float32 [B, Hq, w_obs] device tensor per group (normaliser hand-over).
+        ``k_groups``: None, or [n_groups][batch] windows to keep per group."""
         w = self.w
         W.wkv_compress_groups(self.problem, w.n_groups, w.gamma, self.q, lse, self.k, self.v, self.k_out, self.v_out,
-                              self.win_idx, self.tok_idx, self.n_keep, self.workspace)
+                              self.win_idx, self.tok_idx, self.n_keep, self.workspace, k_windows_groups=k_groups)
         torch.cuda.synchronize()
 
     def oracle_lse(self, g: int) -> torch.Tensor:

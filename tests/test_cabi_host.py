@@ -98,8 +98,25 @@ def test_stage_calls_validate_before_any_launch():
     arr = (C.c_void_p * 1)(4096)
     assert lib.wkv_gather_group(p.ref(), 0, arr, arr, fake, fake, arr, arr, null) == W.WKV_ERR_INVALID_ARG
     assert lib.wkv_gather_group(p.ref(), 65, arr, arr, fake, fake, arr, arr, null) == W.WKV_ERR_INVALID_ARG
-    assert lib.wkv_compress_groups(p.ref(), 8, 9, arr, None, arr, arr, arr, arr, fake, fake, fake, fake, 1 << 30,
+    assert lib.wkv_compress_groups(p.ref(), 8, 9, arr, None, None, arr, arr, arr, arr, fake, fake, fake, fake, 1 << 30,
                                    null) == W.WKV_ERR_INVALID_ARG
+
+
+def test_per_group_budgets_are_validated_on_the_host():
+    # k_windows_groups: every entry within [0, k_windows[b]] (the capacity); caught before any launch
+    lib = W.lib()
+    p = _problem(seq_len=[4096, 2048], win=[8, 8], top_p=[8, 8], k_windows=[64, 32])
+    null, fake = C.c_void_p(0), C.c_void_p(4096)
+    arr = (C.c_void_p * 2)(4096, 4096)
+
+    def call(ks):
+        kg = (C.c_int32 * len(ks))(*ks)
+        return lib.wkv_compress_groups(p.ref(), 2, 1, arr, None, kg, arr, arr, arr, arr, fake, fake, fake, null, 0, null)
+
+    assert call([64, 32, 65, 0]) == W.WKV_ERR_INVALID_ARG and b"k_windows_groups[1][0]" in lib.wkv_last_error()
+    assert call([64, 33, 1, 1]) == W.WKV_ERR_INVALID_ARG
+    assert call([0, -1, 1, 1]) == W.WKV_ERR_INVALID_ARG
+    assert call([64, 32, 0, 7]) == W.WKV_ERR_WORKSPACE      # the budgets pass; the missing workspace is next
 
 
 def test_status_strings():

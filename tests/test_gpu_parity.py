@@ -258,6 +258,41 @@ def test_lse_handoff_rejects_partial_arrays(device):
     assert e.value.status == W.WKV_ERR_INVALID_ARG
 
 
+def test_pyramid_budgets_per_group(device):
+    # Section 2.2.3: Eq. 5-7 budgets (lambda = 14) turned into whole windows per group (floor), the
+    # lower groups keeping more; each group is checked against the oracle run with its own k.
+    n_groups, lam = 4, 14.0
+    seq_len, win = [3000, 1111], [8, 16]
+    total = [0.12 * L * n_groups for L in seq_len]            # 12 % of the prefix per group on average
+    budgets = [W.wkv_group_budgets(tb, n_groups, lam) for tb in total]
+    k_groups = [[int(budgets[b][g] // win[b]) for b in range(2)] for g in range(n_groups)]
+    assert k_groups[0][0] > k_groups[-1][0] > 0
+    cap = [max(k_groups[g][b] for g in range(n_groups)) for b in range(2)]
+    w = _mini(seq_len=seq_len, win=win, top_p=[8, 6], k_windows=cap, n_groups=n_groups, gamma=2)
+    st = P.DeviceState(w, device)
+    st.compress(k_groups=k_groups)
+    win_idx = st.win_idx.cpu().numpy(); tok = st.tok_idx.cpu().numpy(); nkeep = st.n_keep.cpu().numpy()
+    for g, b, h in itertools.product(range(n_groups), range(2), range(w.n_kv_heads)):
+        k = k_groups[g][b]
+        what = f"pyramid g{g} b{b} h{h}"
+        G, L = w.q_per_kv, seq_len[b]
+        t, s, sel, idx = O.select_indices(P.host_f64(w, st.q[g][b, h * G:(h + 1) * G]),
+                                          P.host_f64(w, st.k[g * w.gamma][b, h, :L]), win[b], w.top_p[b], k)
+        assert np.all(win_idx[g, b, h, k:] == -1), what + " win_idx padding"
+        same = P.check_selection(s, sel, win_idx[g, b, h, :k], k, what)
+        want_tok = O.token_indices(win_idx[g, b, h, :k], win[b], L, w.w_obs)
+        n = int(nkeep[g, b, h])
+        assert n == len(want_tok) and np.array_equal(tok[g, b, h, :n], want_tok) and np.all(tok[g, b, h, n:] == -1), what
+        if same:
+            assert np.array_equal(tok[g, b, h, :n], idx)
+        rows = torch.from_numpy(tok[g, b, h, :n].astype(np.int64)).to(device)
+        for l in range(w.gamma):
+            layer = g * w.gamma + l
+            assert torch.equal(st.k_out[layer][b, h, :n], st.k[layer][b, h].index_select(0, rows)), what
+            assert torch.equal(st.v_out[layer][b, h, :n], st.v[layer][b, h].index_select(0, rows)), what
+            assert not st.k_out[layer][b, h, n:].any() and not st.v_out[layer][b, h, n:].any(), what + " zero fill"
+
+
 def test_other_layers_do_not_influence_indices(device):
     w = _mini(seq_len=[900], n_groups=1, gamma=3)
     st = P.DeviceState(w, device)
