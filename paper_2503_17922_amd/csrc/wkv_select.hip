@@ -7,78 +7,15 @@
 
 namespace wkv {
 
-// ------------------------------------------------------------------------------------------
-// Eq. 3-4: s_w = sum(Top-p(W_w)) / min(p, win)
-// One thread per window.  The block stages its windows' token scores in LDS (row stride
-// win+1 words, so the per-thread walks hit distinct banks), then each thread either sums its
-// window (p >= size) or sums the elements whose rank is below p.  Ranks are counted, not
-// sorted: element i is kept when fewer than p elements are larger (equal values ordered by
-// position), which needs no data-dependent register indexing.
-// ------------------------------------------------------------------------------------------
 constexpr int POOL_THREADS = 256;
-constexpr int POOL_LDS_FLOATS = 8192 + 256;   // windows_per_block * (win + 1) fits here
-
-__global__ __launch_bounds__(POOL_THREADS) void pool_kernel(Shape s, BatchParams bp,
-                                                            const float *__restrict__ t,
-                                                            float *__restrict__ s_out,
-                                                            int windows_per_block_max) {
-  __shared__ float lds[POOL_LDS_FLOATS];
-  const int bh = blockIdx.y, b = bh / s.Hkv, g = blockIdx.z;
-  const SeqParam sp = bp.seq[b];
-  const int n_review = sp.L - s.w_obs;
-  const int nw = (n_review + sp.win - 1) / sp.win;
-  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
-  const float *trow = t + row * s.t_stride;
-  float *srow = s_out + row * s.nw_max;
-  // windows per block for THIS sequence's window size (<= the launch-wide maximum)
-  int wpb = 8192 / sp.win;
-  if (wpb > POOL_THREADS) wpb = POOL_THREADS;
-  if (wpb > windows_per_block_max) wpb = windows_per_block_max;
-  const int w0 = blockIdx.x * windows_per_block_max;
-  // this block owns windows [w0, w0 + windows_per_block_max); process them in rounds of wpb
-  for (int base = w0; base < w0 + windows_per_block_max && base < s.nw_max; base += wpb) {
-    const int n_here = min(wpb, min(w0 + windows_per_block_max, s.nw_max) - base);
-    const int tok0 = base * sp.win;
-    const int n_tok = n_here * sp.win;
-    __syncthreads();
-    for (int i = threadIdx.x; i < n_tok; i += POOL_THREADS) {
-      const int tok = tok0 + i;
-      const int wl = i / sp.win, off = i - wl * sp.win;
-      lds[wl * (sp.win + 1) + off] = tok < n_review ? trow[tok] : 0.0f;
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < n_here) {
-      const int w = base + threadIdx.x;
-      if (w >= nw) {
-        srow[w] = -INFINITY;
-      } else {
-        const float *v = lds + threadIdx.x * (sp.win + 1);
-        const int size = min(sp.win, n_review - w * sp.win);
-        float acc = 0.0f;
-        if (sp.p >= size) {
-          for (int i = 0; i < size; ++i) acc += v[i];
-        } else {
-          for (int i = 0; i < size; ++i) {
-            const float vi = v[i];
-            int rank = 0;
-            for (int j = 0; j < size; ++j) {
-              const float vj = v[j];
-              rank += (vj > vi) || (vj == vi && j < i);
-            }
-            if (rank < sp.p) acc += vi;
-          }
-        }
-        srow[w] = acc / (float)sp.p;   // sp.p is already min(p, win)
-      }
-    }
-  }
-}
-
 
 // ------------------------------------------------------------------------------------------
+// Eq. 3-4: s_w = sum(Top-p(W_w)) / min(p, win), one thread per window.
 // Register-resident pooling for the common window sizes.  The window's token scores sit in
-// registers (loaded as float4s: a lane reads its window's 4*WIN contiguous bytes), the rank
-// counting is fully unrolled, nothing is indexed dynamically.
+// registers (loaded as float4s: a lane reads its window's 4*WIN contiguous bytes) and are put
+// in descending order by a fully unrolled bitonic network (min/max pairs, nothing indexed
+// dynamically); the score is the sum of the first p.  Which of several equal values counts
+// as "in the top p" does not change that sum.
 // ------------------------------------------------------------------------------------------
 template <int WIN>
 __device__ __forceinline__ float pool_window_regs(const float *__restrict__ trow, int w, int n_review, int p) {
@@ -101,17 +38,27 @@ __device__ __forceinline__ float pool_window_regs(const float *__restrict__ trow
     for (int i = 0; i < WIN; ++i) acc += i < size ? v[i] : 0.0f;
   } else {
 #pragma unroll
-    for (int i = 0; i < WIN; ++i) {
-      int rank = 0;
+    for (int k = 2; k <= WIN; k <<= 1)
 #pragma unroll
-      for (int j = 0; j < WIN; ++j) rank += (v[j] > v[i]) || (v[j] == v[i] && j < i);
-      acc += (rank < p && i < size) ? v[i] : 0.0f;
-    }
+      for (int j = k >> 1; j > 0; j >>= 1)
+#pragma unroll
+        for (int i = 0; i < WIN; ++i) {
+          const int l = i ^ j;
+          if (l > i) {
+            const float lo = fminf(v[i], v[l]), hi = fmaxf(v[i], v[l]);
+            const bool descending = (i & k) == 0;
+            v[i] = descending ? hi : lo;
+            v[l] = descending ? lo : hi;
+          }
+        }
+#pragma unroll
+    for (int i = 0; i < WIN; ++i) acc += i < p ? v[i] : 0.0f;     // p < size: none of these is padding
   }
   return acc / (float)p;
 }
 
-// Any window size: plain loops over global memory (cached; O(size^2) compares).
+// Any window size: plain loops over global memory (cached; O(size^2) compares).  Element i is
+// kept when fewer than p elements are larger, equal values ordered by position.
 __device__ __forceinline__ float pool_window_any(const float *__restrict__ trow, int w, int win, int n_review, int p) {
   const int tok0 = w * win;
   const int size = min(win, n_review - tok0);
@@ -142,8 +89,8 @@ __device__ __forceinline__ float pool_window(const float *__restrict__ trow, int
   }
 }
 
-// One thread per window; used when every sequence's window size has a register kernel.
-__global__ __launch_bounds__(POOL_THREADS) void pool_fast_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
+// One thread per window.
+__global__ __launch_bounds__(POOL_THREADS) void pool_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
                                                                  float *__restrict__ s_out) {
   const int bh = blockIdx.y, b = bh / s.Hkv, g = blockIdx.z;
   const SeqParam sp = bp.seq[b];
@@ -158,14 +105,8 @@ __global__ __launch_bounds__(POOL_THREADS) void pool_fast_kernel(Shape s, BatchP
 hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
                        float *s_out, hipStream_t stream) {
   if (s.nw_max <= 0) return hipSuccess;
-  const int wpb = POOL_THREADS;
-  dim3 grid((s.nw_max + wpb - 1) / wpb, s.B * s.Hkv, n_groups);
-  bool fast = true;
-  for (int b = 0; b < s.B; ++b) fast = fast && (bp.seq[b].win == 8 || bp.seq[b].win == 16 || bp.seq[b].win == 32);
-  if (fast)
-    hipLaunchKernelGGL(pool_fast_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out);
-  else
-    hipLaunchKernelGGL(pool_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out, wpb);
+  dim3 grid((s.nw_max + POOL_THREADS - 1) / POOL_THREADS, s.B * s.Hkv, n_groups);
+  hipLaunchKernelGGL(pool_kernel, grid, dim3(POOL_THREADS), 0, stream, s, bp, t, s_out);
   return hipGetLastError();
 }
 
