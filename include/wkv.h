@@ -180,7 +180,10 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
  *   win_idx_out    device int32 [n_groups, batch, n_kv_heads, k_max]
  *   tok_idx_out    device int32 [n_groups, batch, n_kv_heads, nkeep_max]
  *   n_keep_out     device int32 [n_groups, batch, n_kv_heads]
- * Results are identical to running the four stage calls group by group.
+ * Results equal those of the four stage calls run group by group, except that the fp32
+ * summation order of the softmax normalisers depends on how a launch splits the keys over
+ * workgroups: token scores can differ in their last bits, hence selections only between windows
+ * whose scores agree to fp32 rounding.
  * n_groups <= WKV_MAX_GROUPS, n_groups*gamma <= WKV_MAX_LAYERS.
  */
 wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int32_t gamma,

@@ -155,6 +155,9 @@ ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   pl.n_chunks1 = (int32_t)ceil_div(Lmax, pl.chunk1);
   pl.chunk2 = pick_chunk(bp, s.B, rows_per_seq, s.w_obs, 256, MAX_CHUNK2);
   pl.n_chunks2 = (int32_t)ceil_div(s.t_stride > 0 ? s.t_stride : 1, pl.chunk2);
+  // every pass-2 workgroup re-reads rows * n_chunks1 partials when it folds them itself: worth
+  // it (one launch less) only while that stays a few KB
+  pl.fold_in_pass2 = pl.mfma && pl.n_chunks1 <= 16;
   return pl;
 }
 

@@ -66,6 +66,7 @@ struct ScorePlan {
   int32_t chunk2, n_chunks2;   // score pass (over t_stride)
   int32_t m_pad;               // rows padded to a multiple of 16
   bool mfma;                   // bf16 MFMA kernels (else the generic ones)
+  bool fold_in_pass2;          // MFMA path: pass 2 folds the pass-1 partials itself (few chunks per row)
 };
 
 struct Workspace {

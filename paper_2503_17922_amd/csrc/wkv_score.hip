@@ -207,6 +207,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   // stores inside the loop would share the vector-memory counter with the key prefetch and make
   // every wait for keys also wait for store acknowledgements.
   __shared__ float t_s[PASS == 2 ? MAX_CHUNK2 + 256 : 1];
+  __shared__ float lse_s[PASS == 2 ? MT * 16 : 1];
 
   // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
   // are the ones most likely still held by the memory-side cache.
@@ -237,6 +238,25 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(-INFINITY, 0.0f);
     return;
   }
+  if (PASS == 2) {
+    // The base-2 log-sum-exp of the MT*16 rows, into LDS.  With few chunks per row the workgroup
+    // folds the (m, z) partials of pass 1 itself (TPR adjacent lanes share a row; the loads
+    // overlap the query staging below); otherwise a fold launch or the caller provided them.
+    constexpr int TPR = MF_THREADS / (MT * 16);
+    const int r = threadIdx.x / TPR, part = threadIdx.x % TPR;
+    if (pl.fold_in_pass2) {
+      float m = -INFINITY, z = 0.0f;
+      if (r < s.M) fold_partials_strided(partials + (row * pl.m_pad + r) * pl.n_chunks1, pl.n_chunks1, part, TPR, m, z);
+#pragma unroll
+      for (int off = 1; off < TPR; off <<= 1) {
+        const float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
+        merge_stats(m, z, m2, z2);
+      }
+      if (part == 0) lse_s[r] = r < s.M ? m + fast_log2(z) : INFINITY;      // padded rows: 2^-inf = 0
+    } else if (part == 0) {
+      lse_s[r] = row_lse2(s, pl, gp, lse_g, g, b, h, row, r);
+    }
+  }
   stage_q_fragments<D, MT>(s, gp.q[g], b, h, qfrag);
   __syncthreads();
 
@@ -244,7 +264,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   float lse_r[MT], mref[MT], zsum[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    lse_r[mt] = PASS == 2 ? row_lse2(s, pl, gp, lse_g, g, b, h, row, mt * 16 + col) : 0.0f;
+    lse_r[mt] = PASS == 2 ? lse_s[mt * 16 + col] : 0.0f;
     mref[mt] = -INFINITY;
     zsum[mt] = 0.0f;
   }
@@ -424,11 +444,15 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
-    hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (!pl.fold_in_pass2) {
+      hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
+  ScorePlan pl2 = pl;
+  if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out);
   return hipGetLastError();
 }
 
