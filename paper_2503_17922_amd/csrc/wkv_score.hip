@@ -477,12 +477,10 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   const size_t lds = ((size_t)s.M * D + s.M) * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
+  if (lds > 48 * 1024) {     // beyond the default dynamic-LDS limit: raise it (per device, any thread)
     e = hipFuncSetAttribute((const void *)score_generic_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (WKV_MAX_OBS_ROWS * D + WKV_MAX_OBS_ROWS) * (int)sizeof(float));
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL((score_generic_kernel<T, D>), g2, block, lds, stream, s, bp, gp, pl, lse, t_out);

@@ -283,12 +283,10 @@ __global__ __launch_bounds__(TOPK_THREADS) void select_kernel(Shape s, BatchPara
 hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
                        int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
   const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
-  static bool attr_set = false;
-  if (!attr_set) {
+  if (lds > 48 * 1024) {     // beyond the default dynamic-LDS limit: raise it (per device, any thread)
     hipError_t e = hipFuncSetAttribute((const void *)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        WKV_MAX_WINDOWS * (int)sizeof(uint32_t));
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   dim3 grid(s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL(topk_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, sc, win_idx, tok_idx, n_keep);
@@ -298,12 +296,10 @@ hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, 
 hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *t,
                          int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
   const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
-  static bool attr_set = false;
-  if (!attr_set) {
+  if (lds > 48 * 1024) {     // beyond the default dynamic-LDS limit: raise it (per device, any thread)
     hipError_t e = hipFuncSetAttribute((const void *)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        WKV_MAX_WINDOWS * (int)sizeof(uint32_t));
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   dim3 grid(s.B * s.Hkv, n_groups);
   hipLaunchKernelGGL(select_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, gk, t, win_idx, tok_idx, n_keep);

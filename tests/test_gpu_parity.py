@@ -155,6 +155,7 @@ def _mini(**kw):
     dict(dtype="f32", head_dim=128, seq_len=[900]),
     dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=1, w_obs=64, seq_len=[600]),
     dict(n_groups=1, gamma=1, seq_len=[4097], win=[16], top_p=[8], k_windows=[31]),
+    dict(n_groups=1, gamma=1, seq_len=[20016], win=[1], top_p=[1], k_windows=[700]),   # 20000 windows: >48 KB of LDS keys
 ])
 def test_edge_cases(kw, device):
     run_and_check(_mini(**kw), device)
