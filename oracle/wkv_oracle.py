@@ -28,7 +28,9 @@ Parity pins (tests/test_oracle_pins.py): rows of A sum to 1; a hand-built ration
 zero queries (harmonic numbers) and two-level keys (pins the 1/sqrt(d) scale); mass
 conservation; library pooling routines (mean / max_pool1d / topk); exhaustive search over all
 window subsets; a scalar pure-Python re-derivation on tiny inputs; index_select for the
-gather; scipy's logsumexp and ln(position+1) for the hand-over form of the normaliser.
+gather; scipy's logsumexp and ln(position+1) for the hand-over form of the normaliser;
+torch's scaled_dot_product_attention, the mean of V for zero queries and a one-hot limit for
+the decode step.
 The absolute values of t and s on random data have no printed example in the paper:
 beyond those pins they are "parity unpinned".  The value of p in aggregation mode, the
 partial-window rule and the budget rounding are conventions of this repository (the paper
@@ -190,3 +192,29 @@ def group_budgets(b_total: float, n_groups: int, lam: float) -> np.ndarray:
         return np.asarray([b_total], dtype=np.float64)
     h = np.arange(H, dtype=np.float64)
     return b_bottom - (b_bottom - b_top) / (H - 1) * h
+
+
+# --------------------------------------------------------------------------------------
+# Generation over the compressed cache (Section 3.4 measures it end to end): one decode step
+# --------------------------------------------------------------------------------------
+def decode_step(q_new: np.ndarray, k_kept: np.ndarray, v_kept: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
+                scale: float | None = None):
+    """One generated token on one KV head of one layer: the new token's key and value are
+    appended to the retained cache and its G query heads attend to all of it, new token
+    included (Eq. 1 with a single query row; nothing is masked).
+
+    q_new: [G, d]; k_kept, v_kept: [n, d] retained rows; k_new, v_new: [d].
+    Returns (out [G, d], K' [n+1, d], V' [n+1, d]).
+    """
+    q_new = np.asarray(q_new, dtype=np.float64)
+    K = np.concatenate([np.asarray(k_kept, dtype=np.float64), np.asarray(k_new, dtype=np.float64)[None, :]], axis=0)
+    V = np.concatenate([np.asarray(v_kept, dtype=np.float64), np.asarray(v_new, dtype=np.float64)[None, :]], axis=0)
+    d = q_new.shape[1]
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty_like(q_new)
+    for g in range(q_new.shape[0]):
+        logits = (K @ q_new[g]) * scale
+        e = np.exp(logits - logits.max())
+        out[g] = (e / e.sum()) @ V
+    return out, K, V

@@ -294,6 +294,40 @@ def test_planted_aligned_span_is_selected():
 # ---------------------------------------------------------------------------------------
 # Eq. 5-7 closed forms
 # ---------------------------------------------------------------------------------------
+def test_decode_step_matches_torch_sdpa():
+    rng = np.random.default_rng(21)
+    n, d, G = 37, 16, 3
+    q = rng.standard_normal((G, d)); kk = rng.standard_normal((n, d)); vv = rng.standard_normal((n, d))
+    kn = rng.standard_normal(d); vn = rng.standard_normal(d)
+    out, K, V = O.decode_step(q, kk, vv, kn, vn)
+    assert K.shape == (n + 1, d) and np.array_equal(K[-1], kn) and np.array_equal(V[-1], vn) and np.array_equal(K[:n], kk)
+    tq = torch.from_numpy(q)[None, :, None, :]                      # [1, G, 1, d]: G heads, one query each
+    tk = torch.from_numpy(K)[None, None].expand(1, G, n + 1, d)
+    tv = torch.from_numpy(V)[None, None].expand(1, G, n + 1, d)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0].numpy()
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-14)
+    out2, _, _ = O.decode_step(q, kk, vv, kn, vn, scale=0.3)
+    want2 = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=0.3)[0, :, 0].numpy()
+    np.testing.assert_allclose(out2, want2, rtol=1e-12, atol=1e-14)
+
+
+def test_decode_step_closed_forms():
+    rng = np.random.default_rng(22)
+    n, d = 9, 8
+    kk = rng.standard_normal((n, d)); vv = rng.standard_normal((n, d)); kn = rng.standard_normal(d); vn = rng.standard_normal(d)
+    # a zero query weighs every token equally: the output is the mean of all n+1 values
+    out, _, V = O.decode_step(np.zeros((2, d)), kk, vv, kn, vn)
+    np.testing.assert_allclose(out, np.broadcast_to(V.mean(axis=0), (2, d)), rtol=1e-13)
+    # an empty retained cache: the token attends to itself only
+    out, _, _ = O.decode_step(rng.standard_normal((2, d)), np.zeros((0, d)), np.zeros((0, d)), kn, vn)
+    np.testing.assert_allclose(out, np.broadcast_to(vn, (2, d)), rtol=1e-15)
+    # a query far along one key: the output tends to that key's value
+    q = 200.0 * kk[4][None, :] / np.linalg.norm(kk[4])
+    kk2 = kk.copy(); kk2[4] *= 10.0
+    out, _, _ = O.decode_step(q, kk2, vv, kn, vn, scale=1.0)
+    np.testing.assert_allclose(out[0], vv[4], atol=1e-9)
+
+
 @pytest.mark.parametrize("H,lam,total", [(4, 14, 8192.0), (8, 14, 4096.0 * 8), (7, 3, 1000.0)])
 def test_group_budgets_closed_forms(H, lam, total):
     b = O.group_budgets(total, H, lam)
