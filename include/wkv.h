@@ -225,6 +225,44 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
 wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
                              double *budgets_out);
 
+/*
+ * Generation over the compact cache (what the throughput test of Section 3.4 runs): one decode
+ * step of one layer.  For every (sequence b, KV head h) with n = n_valid[b,h] retained rows, the
+ * new token's key and value rows are appended at row n of the compact caches, and each of the
+ * G = n_q_heads / n_kv_heads query heads of h attends to rows 0 .. n (the new one included):
+ *     out = softmax(q . K^T * scale) . V      (Eq. 1 with one query row; nothing is masked)
+ * with fp32 accumulation and an fp32 result.
+ */
+typedef struct {
+  int32_t batch;            /* >= 1; batch * n_kv_heads <= 65535                               */
+  int32_t n_q_heads;        /* multiple of n_kv_heads, at most 8 query heads per KV head       */
+  int32_t n_kv_heads;
+  int32_t head_dim;         /* 64 or 128                                                       */
+  int32_t dtype;            /* wkv_dtype of q_new, k_new, v_new and the caches                 */
+  float   scale;            /* logit scale; 0 selects 1/sqrt(head_dim)                         */
+  int32_t capacity;         /* token rows per (b, h) in the caches (nkeep_max + tokens to come) */
+  int64_t cache_stride_b, cache_stride_h, cache_stride_t;   /* elements; head_dim contiguous   */
+} wkv_decode_shape;
+
+/* Bytes of 256-byte-aligned device workspace wkv_decode_step needs; 0 for an invalid shape. */
+size_t wkv_decode_workspace_bytes(const wkv_decode_shape *shape);
+
+/*
+ *   q_new          device [batch, n_q_heads, head_dim], contiguous
+ *   k_new, v_new   device [batch, n_kv_heads, head_dim], contiguous
+ *   k_cache,
+ *   v_cache        device [batch, n_kv_heads, capacity, head_dim] by the strides above; rows
+ *                  0 .. n_valid[b,h]-1 are read, row n_valid[b,h] is written
+ *   n_valid        device int32 [batch, n_kv_heads]; read, then incremented by one (the n_keep
+ *                  array of the compression calls can be passed as it is)
+ *   out            device float32 [batch, n_q_heads, head_dim]
+ * A (b, h) whose n_valid is negative or already equals capacity cannot take the new row: its
+ * caches and n_valid are left untouched and its rows of `out` are set to NaN.
+ */
+wkv_status wkv_decode_step(const wkv_decode_shape *shape, const void *q_new, const void *k_new,
+                           const void *v_new, void *k_cache, void *v_cache, int32_t *n_valid,
+                           float *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 const char *wkv_status_string(wkv_status status);
 
 /* Message describing the most recent failure on the calling thread ("" if none). */

@@ -23,7 +23,7 @@ STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
 
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
            "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string",
-           "wkv_last_error")
+           "wkv_last_error", "wkv_decode_workspace_bytes", "wkv_decode_step")
 
 
 class WkvError(RuntimeError):
@@ -43,6 +43,12 @@ class _Problem(C.Structure):
         ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_t", C.c_int64),
         ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64), ("out_stride_t", C.c_int64),
     ]
+
+
+class _DecodeShape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("scale", C.c_float), ("capacity", C.c_int32),
+                ("cache_stride_b", C.c_int64), ("cache_stride_h", C.c_int64), ("cache_stride_t", C.c_int64)]
 
 
 class Dims(C.Structure):
@@ -79,6 +85,9 @@ def lib() -> C.CDLL:
     l.wkv_compress_groups_profiled.restype = C.c_int
     l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
     l.wkv_group_budgets.restype = C.c_int
+    DP = C.POINTER(_DecodeShape)
+    l.wkv_decode_workspace_bytes.argtypes = [DP]; l.wkv_decode_workspace_bytes.restype = C.c_size_t
+    l.wkv_decode_step.argtypes = [DP, VP, VP, VP, VP, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_decode_step.restype = C.c_int
     l.wkv_status_string.argtypes = [C.c_int]; l.wkv_status_string.restype = C.c_char_p
     l.wkv_last_error.argtypes = []; l.wkv_last_error.restype = C.c_char_p
     _lib = l
@@ -211,6 +220,33 @@ def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, 
     is the trailing keyword here: a nested [n_groups][batch] sequence of ints, or None."""
     CompressCall(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
                  v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, k_windows_groups)(stream)
+
+
+class DecodeShape:
+    """Mirrors ``wkv_decode_shape``.  ``cache_strides`` in elements; ``None`` selects contiguous
+    ``[B, Hkv, capacity, d]`` caches."""
+
+    def __init__(self, *, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, capacity: int,
+                 scale: float = 0.0, cache_strides=None):
+        cache_strides = cache_strides or (n_kv_heads * capacity * head_dim, capacity * head_dim, head_dim)
+        self.c = _DecodeShape(batch, n_q_heads, n_kv_heads, head_dim, dtype, scale, capacity, *cache_strides)
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def wkv_decode_workspace_bytes(shape: DecodeShape) -> int:
+    n = lib().wkv_decode_workspace_bytes(shape.ref())
+    if n == 0:
+        raise WkvError(WKV_ERR_INVALID_ARG, lib().wkv_last_error().decode())
+    return int(n)
+
+
+def wkv_decode_step(shape: DecodeShape, q_new, k_new, v_new, k_cache, v_cache, n_valid, out, workspace,
+                    stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().wkv_decode_step(shape.ref(), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                 _ptr(n_valid), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwkv.so")
-SOURCES = ["wkv_host.cpp", "wkv_api.cpp", "wkv_score.hip", "wkv_select.hip", "wkv_gather.hip"]
+SOURCES = ["wkv_host.cpp", "wkv_api.cpp", "wkv_score.hip", "wkv_select.hip", "wkv_gather.hip", "wkv_decode.hip"]
 
 
 def hipcc() -> str:

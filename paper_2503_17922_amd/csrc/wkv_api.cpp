@@ -243,4 +243,27 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
   return st;
 }
 
+wkv_status wkv_decode_step(const wkv_decode_shape *shape, const void *q_new, const void *k_new, const void *v_new,
+                           void *k_cache, void *v_cache, int32_t *n_valid, float *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream) {
+  Decode dc;
+  wkv_status st = validate_decode(shape, &dc);
+  if (st != WKV_OK) return st;
+  if (!q_new || !k_new || !v_new || !k_cache || !v_cache || !n_valid || !out) {
+    set_error("q_new / k_new / v_new / k_cache / v_cache / n_valid / out is NULL"); return WKV_ERR_INVALID_ARG;
+  }
+  if (misaligned(q_new, 16) || misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(k_cache, 16) ||
+      misaligned(v_cache, 16)) {
+    set_error("q_new, k_new, v_new and the caches must be 16-byte aligned"); return WKV_ERR_INVALID_ARG;
+  }
+  if (!workspace) { set_error("workspace is NULL"); return WKV_ERR_WORKSPACE; }
+  if (misaligned(workspace, 256)) { set_error("workspace must be 256-byte aligned"); return WKV_ERR_WORKSPACE; }
+  if (workspace_bytes < dc.ws_bytes) {
+    set_error("workspace has %zu bytes, %zu needed", workspace_bytes, dc.ws_bytes); return WKV_ERR_WORKSPACE;
+  }
+  hipError_t e = launch_decode(dc.shape, q_new, k_new, v_new, k_cache, v_cache, n_valid, out, (float *)workspace,
+                               (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_decode_step launch");
+}
+
 }  // extern "C"

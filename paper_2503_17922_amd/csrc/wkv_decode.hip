@@ -1,0 +1,287 @@
+// One decode step over the compact cache: the new token's K/V row is appended and its query
+// heads attend to every retained row (softmax(q.K^T * scale).V, nothing masked).
+//
+// With one query row per head this is a matrix-vector product per KV head: every K and V row
+// is read once and used for G = Hq/Hkv dot products, so the step is bound by the HBM stream of
+// the two caches and runs on the plain vector ALU (no MFMA: a G-row operand would leave the
+// matrix pipe 3/4 empty and its operand layout would force V through a transpose).
+//
+//   partial kernel  grid (splits, B*Hkv): a workgroup walks one key range of one KV head.  A
+//                   16-byte piece of a row per lane, so D*esize/16 lanes cover a row and a wave
+//                   load instruction reads 64/that many consecutive rows (fully coalesced).  Each
+//                   lane group keeps its own online-softmax state (running max, sum, output
+//                   piece) per query head, so nothing crosses lanes inside the loop except the
+//                   dot-product reduction within a row's lanes; lane groups, then waves, merge
+//                   once at the end and the workgroup writes (m, l, o) to the workspace.
+//   combine kernel  grid (B*Hkv): merges the splits, normalises, writes fp32 output, bumps the
+//                   row count.
+#include "wkv_device.h"
+
+namespace wkv {
+
+constexpr int DEC_THREADS = 256;
+constexpr int DEC_WAVES = DEC_THREADS / 64;
+constexpr int DEC_U = 4;            // row tiles per wave batch (loads in flight: 2 * DEC_U per lane)
+
+template <typename T> struct Piece;           // the 16-byte piece of a row held by one lane
+template <> struct Piece<uint16_t> {
+  static constexpr int E = 8;
+  static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8]) {
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <> struct Piece<float> {
+  static constexpr int E = 4;
+  static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[4]) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+// Sum over the LPK (8, 16 or 32) adjacent lanes that hold one row; every lane gets the total.
+template <int LPK>
+__device__ __forceinline__ float row_lanes_sum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, false)); // row_half_mirror
+  if (LPK >= 16)
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, false)); // row_mirror
+  if (LPK >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+// Merge the online-softmax state (m2, l2, o2) into (m, l, o); all in base 2.
+template <int E>
+__device__ __forceinline__ void merge_state(float &m, float &l, float (&o)[E], float m2, float l2, const float (&o2)[E]) {
+  const float mn = fmaxf(m, m2);
+  if (mn == -INFINITY) return;                      // both empty
+  const float a = fast_exp2(m - mn), b = fast_exp2(m2 - mn);
+  l = l * a + l2 * b;
+#pragma unroll
+  for (int c = 0; c < E; ++c) o[c] = o[c] * a + o2[c] * b;
+  m = mn;
+}
+
+// Partial result of one (row of the grid, split): per query head g, D output channels then m, l.
+__device__ __forceinline__ int64_t part_offset(const DecodeShape &s, int bh, int split, int g) {
+  return (((int64_t)bh * s.n_splits + split) * s.G + g) * (s.d + 2);
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeShape s, const T *__restrict__ q_new,
+                                                                     const T *__restrict__ k_new,
+                                                                     const T *__restrict__ v_new, T *k_cache, T *v_cache,
+                                                                     const int32_t *__restrict__ n_valid,
+                                                                     float *__restrict__ part) {
+  constexpr int E = Piece<T>::E;
+  constexpr int LPK = D / E;                 // lanes per row
+  constexpr int KPT = 64 / LPK;              // rows per wave load instruction
+  __shared__ float wave_state[DEC_WAVES][G][D + 2];
+
+  const int bh = blockIdx.y, b = bh / s.Hkv, h = bh % s.Hkv, split = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int slot = lane / LPK, piece = lane % LPK;
+  const int n = n_valid[bh];
+  const bool usable = n >= 0 && n < s.capacity;       // room for the new row
+  const int n_total = usable ? n + 1 : 0;             // rows attended to, the new one last
+
+  T *kc = k_cache + (int64_t)b * s.sb + (int64_t)h * s.sh;
+  T *vc = v_cache + (int64_t)b * s.sb + (int64_t)h * s.sh;
+  const T *kn = k_new + ((int64_t)b * s.Hkv + h) * D;
+  const T *vn = v_new + ((int64_t)b * s.Hkv + h) * D;
+
+  // append: the first workgroup of the row copies the new K/V row into the caches.  Nobody
+  // reads it from there in this launch (the new row is always taken from k_new / v_new).
+  if (split == 0 && usable && threadIdx.x < 2 * LPK) {
+    const int pc = threadIdx.x % LPK;
+    if (threadIdx.x < LPK) *(uint4 *)(kc + (int64_t)n * s.st + pc * E) = *(const uint4 *)(kn + pc * E);
+    else *(uint4 *)(vc + (int64_t)n * s.st + pc * E) = *(const uint4 *)(vn + pc * E);
+  }
+
+  // this lane's piece of the G query rows, pre-multiplied by scale * log2(e)
+  float qv[G][E];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float f[E];
+    Piece<T>::unpack(*(const uint4 *)(q_new + ((int64_t)b * s.Hq + (int64_t)h * G + g) * D + piece * E), f);
+#pragma unroll
+    for (int c = 0; c < E; ++c) qv[g][c] = f[c] * s.c1;
+  }
+
+  float m[G], l[G], o[G][E];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -INFINITY; l[g] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < E; ++c) o[g][c] = 0.0f;
+  }
+
+  const int c0 = split * s.chunk, cend = min(c0 + s.chunk, n_total);
+  // rows of this wave: tiles of KPT rows, tile index wave, wave + DEC_WAVES, ...; DEC_U tiles per batch
+  auto row_ptr = [&](const T *cache, const T *fresh, int j) -> const uint4 * {
+    // rows below n live in the cache; row n (and anything clamped past the end) is the new one
+    return (const uint4 *)(j < n ? cache + (int64_t)j * s.st + piece * E : fresh + piece * E);
+  };
+  uint4 kr[DEC_U], vr[DEC_U];
+  auto load_batch = [&](int t0) {
+#pragma unroll
+    for (int u = 0; u < DEC_U; ++u) {
+      const int j = c0 + (t0 + u * DEC_WAVES) * KPT + slot;
+      kr[u] = *row_ptr(kc, kn, j);
+      vr[u] = *row_ptr(vc, vn, j);
+    }
+  };
+  int t0 = wave;
+  if (c0 < cend) load_batch(t0);
+  for (; c0 + t0 * KPT < cend; t0 += DEC_U * DEC_WAVES) {
+    uint4 kcur[DEC_U], vcur[DEC_U];
+#pragma unroll
+    for (int u = 0; u < DEC_U; ++u) { kcur[u] = kr[u]; vcur[u] = vr[u]; }
+    load_batch(t0 + DEC_U * DEC_WAVES);          // next batch (addresses clamp to the new row past the end)
+
+    float sc[DEC_U][G];
+#pragma unroll
+    for (int u = 0; u < DEC_U; ++u) {
+      float kf[E];
+      Piece<T>::unpack(kcur[u], kf);
+      const int j = c0 + (t0 + u * DEC_WAVES) * KPT + slot;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float a = 0.0f;
+#pragma unroll
+        for (int c = 0; c < E; ++c) a = fmaf(qv[g][c], kf[c], a);
+        a = row_lanes_sum<LPK>(a);
+        sc[u][g] = j < cend ? a : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float bm = sc[0][g];
+#pragma unroll
+      for (int u = 1; u < DEC_U; ++u) bm = fmaxf(bm, sc[u][g]);
+      const float mn = fmaxf(m[g], bm);
+      if (mn != -INFINITY) {
+        const float corr = fast_exp2(m[g] - mn);    // m = -inf: 0
+        m[g] = mn;
+        l[g] *= corr;
+#pragma unroll
+        for (int c = 0; c < E; ++c) o[g][c] *= corr;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < DEC_U; ++u) {
+      float vf[E];
+      Piece<T>::unpack(vcur[u], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = m[g] == -INFINITY ? 0.0f : fast_exp2(sc[u][g] - m[g]);
+        l[g] += p;
+#pragma unroll
+        for (int c = 0; c < E; ++c) o[g][c] = fmaf(p, vf[c], o[g][c]);
+      }
+    }
+  }
+
+  // merge the KPT lane groups of the wave (lanes with equal piece)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int off = LPK; off < 64; off <<= 1) {
+      float o2[E];
+      const float m2 = __shfl_xor(m[g], off), l2 = __shfl_xor(l[g], off);
+#pragma unroll
+      for (int c = 0; c < E; ++c) o2[c] = __shfl_xor(o[g][c], off);
+      merge_state<E>(m[g], l[g], o[g], m2, l2, o2);
+    }
+    if (slot == 0) {
+#pragma unroll
+      for (int c = 0; c < E; ++c) wave_state[wave][g][piece * E + c] = o[g][c];
+      if (piece == 0) { wave_state[wave][g][D] = m[g]; wave_state[wave][g][D + 1] = l[g]; }
+    }
+  }
+  __syncthreads();
+  // merge the waves: one thread per (head, channel); the statistics are recomputed per thread
+  for (int i = threadIdx.x; i < G * D; i += DEC_THREADS) {
+    const int g = i / D, c = i % D;
+    float mm = wave_state[0][g][D];
+#pragma unroll
+    for (int w = 1; w < DEC_WAVES; ++w) mm = fmaxf(mm, wave_state[w][g][D]);
+    float ll = 0.0f, oo = 0.0f;
+    if (mm != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < DEC_WAVES; ++w) {
+        const float a = fast_exp2(wave_state[w][g][D] - mm);
+        ll += wave_state[w][g][D + 1] * a;
+        oo += wave_state[w][g][c] * a;
+      }
+    }
+    float *dst = part + part_offset(s, bh, split, g);
+    dst[c] = oo;
+    if (c == 0) { dst[D] = mm; dst[D + 1] = ll; }
+  }
+}
+
+__global__ __launch_bounds__(DEC_THREADS) void decode_combine_kernel(DecodeShape s, const float *__restrict__ part,
+                                                                     int32_t *n_valid, float *__restrict__ out) {
+  const int bh = blockIdx.x, b = bh / s.Hkv, h = bh % s.Hkv;
+  const int D = s.d;
+  for (int i = threadIdx.x; i < s.G * D; i += DEC_THREADS) {
+    const int g = i / D, c = i % D;
+    float mm = -INFINITY;
+    for (int sp = 0; sp < s.n_splits; ++sp) mm = fmaxf(mm, part[part_offset(s, bh, sp, g) + D]);
+    float ll = 0.0f, oo = 0.0f;
+    if (mm != -INFINITY) {
+      for (int sp = 0; sp < s.n_splits; ++sp) {
+        const float *p = part + part_offset(s, bh, sp, g);
+        const float a = fast_exp2(p[D] - mm);
+        ll += p[D + 1] * a;
+        oo += p[c] * a;
+      }
+    }
+    // no row could be attended to (the cache is full or its count is invalid): NaN marks it
+    out[((int64_t)b * s.Hq + (int64_t)h * s.G + g) * D + c] = ll > 0.0f ? oo / ll : __uint_as_float(0x7fc00000u);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int n = n_valid[bh];
+    if (n >= 0 && n < s.capacity) n_valid[bh] = n + 1;
+  }
+}
+
+template <typename T, int D>
+static hipError_t launch_partial(const DecodeShape &s, const void *q, const void *kn, const void *vn, void *kc,
+                                 void *vc, const int32_t *n_valid, float *part, hipStream_t stream) {
+  dim3 grid(s.n_splits, s.B * s.Hkv), block(DEC_THREADS);
+#define WKV_DEC_CASE(GG)                                                                                          \
+  case GG:                                                                                                        \
+    hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), grid, block, 0, stream, s, (const T *)q, (const T *)kn, \
+                       (const T *)vn, (T *)kc, (T *)vc, n_valid, part);                                           \
+    break;
+  switch (s.G) {
+    WKV_DEC_CASE(1) WKV_DEC_CASE(2) WKV_DEC_CASE(3) WKV_DEC_CASE(4) WKV_DEC_CASE(5) WKV_DEC_CASE(6)
+    WKV_DEC_CASE(7) WKV_DEC_CASE(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef WKV_DEC_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const DecodeShape &s, const void *q_new, const void *k_new, const void *v_new, void *k_cache,
+                         void *v_cache, int32_t *n_valid, float *out, float *part, hipStream_t stream) {
+  hipError_t e;
+  if (s.dtype == WKV_BF16)
+    e = s.d == 128 ? launch_partial<uint16_t, 128>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream)
+                   : launch_partial<uint16_t, 64>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream);
+  else
+    e = s.d == 128 ? launch_partial<float, 128>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream)
+                   : launch_partial<float, 64>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(s.B * s.Hkv), dim3(DEC_THREADS), 0, stream, s, part, n_valid, out);
+  return hipGetLastError();
+}
+
+}  // namespace wkv

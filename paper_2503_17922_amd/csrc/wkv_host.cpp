@@ -1,6 +1,7 @@
 // Host-side logic of libwkv: argument validation, derived sizes, launch planning and the
 // scalar helpers.  Nothing in this file touches the GPU, so all of it is testable on a
 // machine without one.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -179,6 +180,53 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_group
   return w;
 }
 
+wkv_status validate_decode(const wkv_decode_shape *p, Decode *out) {
+  g_err[0] = 0;
+  if (!p) { set_error("shape is NULL"); return WKV_ERR_INVALID_ARG; }
+  if (p->batch < 1) { set_error("batch must be >= 1 (got %d)", p->batch); return WKV_ERR_INVALID_ARG; }
+  if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) {
+    set_error("n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
+    return WKV_ERR_INVALID_ARG;
+  }
+  if ((int64_t)p->batch * p->n_kv_heads > 65535) {
+    set_error("batch * n_kv_heads exceeds 65535 (launch grid limit); split the call"); return WKV_ERR_UNSUPPORTED;
+  }
+  const int32_t G = p->n_q_heads / p->n_kv_heads;
+  if (G > 8) { set_error("n_q_heads / n_kv_heads = %d is not supported by the decode step (at most 8)", G); return WKV_ERR_UNSUPPORTED; }
+  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16) { set_error("unknown dtype %d", p->dtype); return WKV_ERR_INVALID_ARG; }
+  if (p->head_dim != 64 && p->head_dim != 128) {
+    set_error("head_dim %d is not supported (64 or 128)", p->head_dim); return WKV_ERR_UNSUPPORTED;
+  }
+  if (!(p->scale >= 0.0f) || std::isinf(p->scale)) {
+    set_error("scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))"); return WKV_ERR_INVALID_ARG;
+  }
+  if (p->capacity < 1) { set_error("capacity must be >= 1"); return WKV_ERR_INVALID_ARG; }
+  const int64_t vec = p->dtype == WKV_BF16 ? 8 : 4;
+  const int64_t strides[3] = {p->cache_stride_b, p->cache_stride_h, p->cache_stride_t};
+  for (int i = 0; i < 3; ++i)
+    if (strides[i] < 0 || strides[i] % vec != 0) {
+      set_error("cache strides must be non-negative multiples of %lld elements (16 bytes)", (long long)vec);
+      return WKV_ERR_INVALID_ARG;
+    }
+  if (p->cache_stride_t < p->head_dim || p->cache_stride_h < p->head_dim) {
+    set_error("cache token and head strides must be >= head_dim"); return WKV_ERR_INVALID_ARG;
+  }
+  DecodeShape &s = out->shape;
+  s.B = p->batch; s.Hq = p->n_q_heads; s.Hkv = p->n_kv_heads; s.d = p->head_dim; s.G = G; s.dtype = p->dtype;
+  s.capacity = p->capacity;
+  const double scale = p->scale > 0.0f ? (double)p->scale : 1.0 / std::sqrt((double)p->head_dim);
+  s.c1 = (float)(scale * 1.4426950408889634074);
+  s.sb = p->cache_stride_b; s.sh = p->cache_stride_h; s.st = p->cache_stride_t;
+  // about 1024 workgroups over the launch, key ranges of at least 256 rows (multiples of 64)
+  const int64_t rows = (int64_t)s.B * s.Hkv;
+  int64_t splits = std::min<int64_t>(std::max<int64_t>(ceil_div(1024, rows), 1), 64);
+  int64_t chunk = std::max<int64_t>(ceil_div(ceil_div(s.capacity, splits), 64) * 64, 256);
+  s.chunk = (int32_t)chunk;
+  s.n_splits = (int32_t)ceil_div(s.capacity, chunk);
+  out->ws_bytes = (size_t)rows * s.n_splits * s.G * (s.d + 2) * sizeof(float);
+  return WKV_OK;
+}
+
 }  // namespace wkv
 
 using namespace wkv;
@@ -198,6 +246,12 @@ size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups) {
   fill_shape(problem, dm, &s, &bp);
   ScorePlan pl = plan_score(s, bp, n_groups);
   return carve_workspace(s, pl, n_groups, nullptr).bytes;
+}
+
+size_t wkv_decode_workspace_bytes(const wkv_decode_shape *shape) {
+  Decode dc;
+  if (validate_decode(shape, &dc) != WKV_OK) return 0;
+  return dc.ws_bytes;
 }
 
 wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda, double *budgets_out) {

@@ -100,4 +100,20 @@ hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk
 hipError_t launch_gather(const Shape &s, const LayerPtrs &lp, int32_t n_layers, int32_t gamma,
                          const int32_t *tok_idx, const int32_t *n_keep, hipStream_t stream);
 
+// ---- decode over the compact cache --------------------------------------------------------
+struct DecodeShape {
+  int32_t B, Hq, Hkv, d, G, dtype;
+  int32_t capacity;          // token rows per (sequence, KV head) in the caches
+  int32_t n_splits, chunk;   // key ranges per (sequence, KV head) and their length
+  float c1;                  // scale * log2(e)
+  int64_t sb, sh, st;        // cache strides in elements
+};
+struct Decode {
+  DecodeShape shape;
+  size_t ws_bytes;           // partial results: [B*Hkv][n_splits][G][d + 2] floats
+};
+wkv_status validate_decode(const wkv_decode_shape *p, Decode *out);
+hipError_t launch_decode(const DecodeShape &s, const void *q_new, const void *k_new, const void *v_new, void *k_cache,
+                         void *v_cache, int32_t *n_valid, float *out, float *part, hipStream_t stream);
+
 }  // namespace wkv

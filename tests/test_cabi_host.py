@@ -119,6 +119,28 @@ def test_per_group_budgets_are_validated_on_the_host():
     assert call([64, 32, 0, 7]) == W.WKV_ERR_WORKSPACE      # the budgets pass; the missing workspace is next
 
 
+def test_decode_shape_validation_and_workspace():
+    lib = W.lib()
+    ok = dict(batch=2, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=W.WKV_BF16, capacity=4160)
+    n = W.wkv_decode_workspace_bytes(W.DecodeShape(**ok))
+    assert n > 0 and n % (4 * (128 + 2)) == 0            # [rows][splits][G][d + 2] floats
+    for bad, status in ((dict(n_q_heads=30), W.WKV_ERR_INVALID_ARG), (dict(head_dim=96), W.WKV_ERR_UNSUPPORTED),
+                        (dict(n_q_heads=72), W.WKV_ERR_UNSUPPORTED), (dict(capacity=0), W.WKV_ERR_INVALID_ARG),
+                        (dict(dtype=5), W.WKV_ERR_INVALID_ARG), (dict(cache_strides=(4160 * 128 * 8, 4160 * 128, 100)), W.WKV_ERR_INVALID_ARG),
+                        (dict(scale=-1.0), W.WKV_ERR_INVALID_ARG)):
+        kw = dict(ok); kw.update(bad)
+        sh = W.DecodeShape(**kw)
+        assert lib.wkv_decode_workspace_bytes(sh.ref()) == 0
+        null, fake = C.c_void_p(0), C.c_void_p(4096)
+        assert lib.wkv_decode_step(sh.ref(), fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, null) == status
+    sh = W.DecodeShape(**ok)
+    null, fake = C.c_void_p(0), C.c_void_p(4096)
+    assert lib.wkv_decode_step(sh.ref(), fake, fake, fake, fake, fake, fake, null, fake, 1 << 30, null) == W.WKV_ERR_INVALID_ARG
+    assert lib.wkv_decode_step(sh.ref(), fake, C.c_void_p(4104), fake, fake, fake, fake, fake, fake, 1 << 30, null) == W.WKV_ERR_INVALID_ARG
+    assert lib.wkv_decode_step(sh.ref(), fake, fake, fake, fake, fake, fake, fake, null, 0, null) == W.WKV_ERR_WORKSPACE
+    assert lib.wkv_decode_step(sh.ref(), fake, fake, fake, fake, fake, fake, fake, fake, 64, null) == W.WKV_ERR_WORKSPACE
+
+
 def test_status_strings():
     lib = W.lib()
     seen = {lib.wkv_status_string(s).decode() for s in (0, -1, -2, -3, -4)}

@@ -1,0 +1,114 @@
+"""GPU parity of the decode step over the compact cache: wkv_decode_step (through the C ABI)
+against the fp64 oracle, on caches produced by wkv_compress_groups and on hand-made ones."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_17922_amd as W
+import wkv_synth as S
+from oracle import wkv_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-3, 2e-5     # fp32 accumulation and a hardware exp2 against fp64; values are O(1)
+KIND_DECODE = 9             # generator stream of the new-token tensors
+
+
+def _new_token(w, device, step, what, shape):
+    numel = int(np.prod(shape))
+    return S.normal_torch(w.seed, S.stream_id(KIND_DECODE, step, what), numel, w.dtype, device).view(*shape)
+
+
+def _decode_and_check(w, device, n_steps, extra_rows):
+    """Compress a workload straight into caches with room for ``extra_rows`` more tokens, then
+    generate ``n_steps`` tokens on the first layer and follow every step with the oracle."""
+    base = P.make_problem(w)
+    nk = W.wkv_get_dims(base).nkeep_max
+    cap = nk + extra_rows
+    B, H, Hq, d, G = w.batch, w.n_kv_heads, w.n_q_heads, w.head_dim, w.q_per_kv
+    st = P.DeviceState(w, device)
+    # the compact caches ARE the decode caches: same tensors, strides for `cap` rows
+    st.problem = P.make_problem(w, out_strides=(H * cap * d, cap * d, d))
+    dt = st.k[0].dtype
+    st.k_out = [torch.full((B, H, cap, d), 7.0, dtype=dt, device=device) for _ in range(w.n_layers)]
+    st.v_out = [torch.full((B, H, cap, d), 7.0, dtype=dt, device=device) for _ in range(w.n_layers)]
+    st.compress()
+    layer, g = 0, 0
+    n_valid = st.n_keep[g].clone()                                   # [B, H]
+    shape = W.DecodeShape(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, capacity=cap,
+                          dtype=W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16)
+    ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    out = torch.full((B, Hq, d), -5.0, dtype=torch.float32, device=device)
+    # oracle state: the retained rows of every (b, h), widened exactly
+    n0 = n_valid.cpu().numpy()
+    ok = {(b, h): P.host_f64(w, st.k_out[layer][b, h, : n0[b, h]]) for b in range(B) for h in range(H)}
+    ov = {(b, h): P.host_f64(w, st.v_out[layer][b, h, : n0[b, h]]) for b in range(B) for h in range(H)}
+    for step in range(n_steps):
+        q = _new_token(w, device, step, 0, (B, Hq, d))
+        kn = _new_token(w, device, step, 1, (B, H, d))
+        vn = _new_token(w, device, step, 2, (B, H, d))
+        k_before, v_before = st.k_out[layer].clone(), st.v_out[layer].clone()
+        W.wkv_decode_step(shape, q, kn, vn, st.k_out[layer], st.v_out[layer], n_valid, out, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        nv = n_valid.cpu().numpy()
+        for b, h in itertools.product(range(B), range(H)):
+            want, ok[b, h], ov[b, h] = O.decode_step(P.host_f64(w, q[b, h * G:(h + 1) * G]), ok[b, h], ov[b, h],
+                                                     P.host_f64(w, kn[b, h]), P.host_f64(w, vn[b, h]))
+            n = ok[b, h].shape[0]
+            assert nv[b, h] == n, f"step {step} b{b} h{h}: n_valid {nv[b, h]} != {n}"
+            np.testing.assert_allclose(got[b, h * G:(h + 1) * G], want, rtol=RTOL, atol=ATOL,
+                                       err_msg=f"{w.name} decode step {step} b{b} h{h}")
+            # the appended rows are in the cache, bit for bit, and nothing else moved
+            assert torch.equal(st.k_out[layer][b, h, n - 1], kn[b, h]) and torch.equal(st.v_out[layer][b, h, n - 1], vn[b, h])
+            assert np.array_equal(P.host_f64(w, st.k_out[layer][b, h, :n]), ok[b, h])
+            k_before[b, h, n - 1] = kn[b, h]; v_before[b, h, n - 1] = vn[b, h]
+        assert torch.equal(k_before, st.k_out[layer]) and torch.equal(v_before, st.v_out[layer]), "a row other than the appended one changed"
+    return st, shape, n_valid, out, ws
+
+
+def test_decode_after_compression_bf16(device):
+    # Llama-shaped heads (G = 4, d = 128); two sequences of different length and window size
+    w = S.Workload(name="dec_bf16", seed=91, dtype="bf16", n_groups=1, gamma=2, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                   w_obs=16, seq_len=[3000, 1111], win=[8, 16], top_p=[8, 6], k_windows=[120, 20])
+    _decode_and_check(w, device, n_steps=3, extra_rows=8)
+
+
+def test_decode_full_size_cache(device):
+    # the retained cache of the 32K configuration's shape on one group: 4128 rows per head, 8 KV heads
+    w = S.scaled_workload(S.make_workload("c4"), n_groups=1, gamma=1)
+    _decode_and_check(w, device, n_steps=2, extra_rows=64)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=2, w_obs=8),                 # c1-like, fp32, G = 2
+    dict(dtype="f32", head_dim=128, n_q_heads=3, n_kv_heads=3, w_obs=4),                # G = 1
+    dict(dtype="bf16", head_dim=64, n_q_heads=12, n_kv_heads=2, w_obs=4),               # G = 6, d = 64
+    dict(dtype="bf16", head_dim=128, n_q_heads=16, n_kv_heads=2, w_obs=8),              # G = 8
+    dict(dtype="bf16", head_dim=128, n_q_heads=8, n_kv_heads=2, w_obs=16, seq_len=[16], k_windows=[0]),   # only the observation rows
+])
+def test_decode_shapes(device, kw):
+    base = dict(name="dec_mini", seed=92, dtype="bf16", n_groups=1, gamma=1, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                w_obs=16, seq_len=[700], win=[8], top_p=[8], k_windows=[30])
+    base.update(kw)
+    _decode_and_check(S.Workload(**base), device, n_steps=2, extra_rows=5)
+
+
+def test_decode_full_cache_is_refused_per_row(device):
+    # capacity reached on some rows: those rows are left alone and flagged with NaN, the others proceed
+    w = S.Workload(name="dec_full", seed=93, dtype="bf16", n_groups=1, gamma=1, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                   w_obs=8, seq_len=[400, 200], win=[8, 8], top_p=[8, 8], k_windows=[10, 5])
+    st, shape, n_valid, out, ws = _decode_and_check(w, device, n_steps=1, extra_rows=1)
+    # sequence 0 (10 windows) filled its cache with that one step; sequence 1 still has room
+    cap = shape.c.capacity
+    assert n_valid[0].tolist() == [cap, cap] and max(n_valid[1].tolist()) < cap
+    before_k = st.k_out[0].clone(); before_n = n_valid.clone()
+    q = _new_token(w, device, 50, 0, (2, 4, 128)); kn = _new_token(w, device, 50, 1, (2, 2, 128)); vn = _new_token(w, device, 50, 2, (2, 2, 128))
+    W.wkv_decode_step(shape, q, kn, vn, st.k_out[0], st.v_out[0], n_valid, out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out[0]).all()) and not bool(torch.isnan(out[1]).any())
+    assert torch.equal(n_valid[0], before_n[0]) and torch.equal(n_valid[1], before_n[1] + 1)
+    assert torch.equal(st.k_out[0][0], before_k[0])
