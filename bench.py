@@ -164,6 +164,49 @@ def lse_handoff(args, W, w, st, stream, ab):
             "note": "inputs additionally include lse_obs [B, Hq, w_obs] per group (a by-product of prefill attention)"}
 
 
+def decode_leg(W, w, device, stream, steps):
+    """One decode step of one layer over retained caches of the workload's size (n_keep rows per
+    KV head), for a single sequence (latency) and for 64 sequences (throughput).  Every K and V
+    row is read once per step: algorithmic bytes = 2 * batch * Hkv * rows * head_dim * esize."""
+    import torch
+    out = {}
+    n_rows = w.k_windows[0] * w.win[0] + w.w_obs
+    esize = 2 if w.dtype == "bf16" else 4
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    for batch in (1, 64):
+        cap = n_rows + 64
+        shape = W.DecodeShape(batch=batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              capacity=cap, dtype=W.WKV_BF16 if w.dtype == "bf16" else W.WKV_F32)
+        H, d = w.n_kv_heads, w.head_dim
+        kc = torch.randn((batch, H, cap, d), device=device, dtype=torch.float32).to(tdt)
+        vc = torch.randn((batch, H, cap, d), device=device, dtype=torch.float32).to(tdt)
+        q = torch.randn((batch, w.n_q_heads, d), device=device, dtype=torch.float32).to(tdt)
+        kn = torch.randn((batch, H, d), device=device, dtype=torch.float32).to(tdt)
+        vn = torch.randn((batch, H, d), device=device, dtype=torch.float32).to(tdt)
+        res = torch.empty((batch, w.n_q_heads, d), device=device, dtype=torch.float32)
+        ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
+        n_valid = torch.full((batch, H), n_rows, dtype=torch.int32, device=device)
+
+        def run(n):
+            for _ in range(n):
+                n_valid.fill_(n_rows)            # stay at the same length: the fill is part of the loop for both counts
+                W.wkv_decode_step(shape, q, kn, vn, kc, vc, n_valid, res, ws, stream)
+        run(5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(steps)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        nbytes = 2 * batch * H * (n_rows + 1) * d * esize
+        out[f"batch{batch}"] = {"ms_per_layer_step": round(ms, 4), "algorithmic_bytes": nbytes,
+                                "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                "rows_per_kv_head": n_rows + 1}
+    out["note"] = ("wkv_decode_step on synthetic caches of the retained size; times include one tiny fill kernel "
+                   "per step and the launch overhead of 3 kernels (latency-bound at batch 1)")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -173,6 +216,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-lse-handoff", action="store_true",
                     help="skip the second measurement (softmax normalisers handed over by the caller)")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for hardware counters)")
     args = ap.parse_args()
@@ -267,6 +311,8 @@ def main():
     }
     if not args.no_lse_handoff:
         out["lse_handoff"] = lse_handoff(args, W, w, st, stream, ab)
+    if not args.no_decode:
+        out["decode"] = decode_leg(W, w, device, stream, max(args.steps, 20))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, st)
     print(json.dumps(out))
