@@ -225,27 +225,49 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeShape
   }
 }
 
+constexpr int DEC_MAX_SPLITS = 64;
+
 __global__ __launch_bounds__(DEC_THREADS) void decode_combine_kernel(DecodeShape s, const float *__restrict__ part,
                                                                      int32_t *n_valid, float *__restrict__ out) {
+  // weight of every (head, split) in the merged result: 2^(m_split - m) / l, or 0
+  __shared__ float wgt[8][DEC_MAX_SPLITS];
+  __shared__ float m_s[8][DEC_MAX_SPLITS], l_s[8][DEC_MAX_SPLITS];
   const int bh = blockIdx.x, b = bh / s.Hkv, h = bh % s.Hkv;
   const int D = s.d;
-  for (int i = threadIdx.x; i < s.G * D; i += DEC_THREADS) {
-    const int g = i / D, c = i % D;
-    float mm = -INFINITY;
-    for (int sp = 0; sp < s.n_splits; ++sp) mm = fmaxf(mm, part[part_offset(s, bh, sp, g) + D]);
-    float ll = 0.0f, oo = 0.0f;
-    if (mm != -INFINITY) {
-      for (int sp = 0; sp < s.n_splits; ++sp) {
-        const float *p = part + part_offset(s, bh, sp, g);
-        const float a = fast_exp2(p[D] - mm);
-        ll += p[D + 1] * a;
-        oo += p[c] * a;
-      }
-    }
-    // no row could be attended to (the cache is full or its count is invalid): NaN marks it
-    out[((int64_t)b * s.Hq + (int64_t)h * s.G + g) * D + c] = ll > 0.0f ? oo / ll : __uint_as_float(0x7fc00000u);
+  for (int i = threadIdx.x; i < s.G * s.n_splits; i += DEC_THREADS) {      // all (m, l) pairs at once
+    const int g = i / s.n_splits, sp = i % s.n_splits;
+    const float *p = part + part_offset(s, bh, sp, g);
+    m_s[g][sp] = p[D];
+    l_s[g][sp] = p[D + 1];
   }
   __syncthreads();
+  if (threadIdx.x < s.G) {
+    const int g = threadIdx.x;
+    float mm = -INFINITY, ll = 0.0f;
+    for (int sp = 0; sp < s.n_splits; ++sp) mm = fmaxf(mm, m_s[g][sp]);
+    for (int sp = 0; sp < s.n_splits; ++sp) {
+      const float a = mm == -INFINITY ? 0.0f : fast_exp2(m_s[g][sp] - mm);
+      wgt[g][sp] = a;
+      ll += l_s[g][sp] * a;
+    }
+    // no row could be attended to (the cache is full or its count is invalid): NaN marks it
+    const float inv = ll > 0.0f ? 1.0f / ll : __uint_as_float(0x7fc00000u);
+    for (int sp = 0; sp < s.n_splits; ++sp) wgt[g][sp] *= inv;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < s.G * D; i += DEC_THREADS) {
+    const int g = i / D, c = i % D;
+    const float *p = part + part_offset(s, bh, 0, g) + c;
+    const int64_t stride = (int64_t)s.G * (D + 2);                         // between the splits of one head
+    float oo = 0.0f;
+    int sp = 0;
+    for (; sp + 4 <= s.n_splits; sp += 4) {                                 // four independent loads in flight
+      const float a0 = p[sp * stride], a1 = p[(sp + 1) * stride], a2 = p[(sp + 2) * stride], a3 = p[(sp + 3) * stride];
+      oo += a0 * wgt[g][sp] + a1 * wgt[g][sp + 1] + a2 * wgt[g][sp + 2] + a3 * wgt[g][sp + 3];
+    }
+    for (; sp < s.n_splits; ++sp) oo += p[sp * stride] * wgt[g][sp];
+    out[((int64_t)b * s.Hq + (int64_t)h * s.G + g) * D + c] = oo;
+  }
   if (threadIdx.x == 0) {
     const int n = n_valid[bh];
     if (n >= 0 && n < s.capacity) n_valid[bh] = n + 1;
