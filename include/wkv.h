@@ -226,7 +226,7 @@ wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
                              double *budgets_out);
 
 /*
- * Generation over the compact cache (what the throughput test of Section 3.4 runs): one decode
+ * Generation over the compact cache (what the throughput test of Section 3.5 runs): one decode
  * step of one layer.  For every (sequence b, KV head h) with n = n_valid[b,h] retained rows, the
  * new token's key and value rows are appended at row n of the compact caches, and each of the
  * G = n_q_heads / n_kv_heads query heads of h attends to rows 0 .. n (the new one included):

@@ -195,7 +195,7 @@ def group_budgets(b_total: float, n_groups: int, lam: float) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------
-# Generation over the compressed cache (Section 3.4 measures it end to end): one decode step
+# Generation over the compressed cache (Section 3.5 measures it end to end): one decode step
 # --------------------------------------------------------------------------------------
 def decode_step(q_new: np.ndarray, k_kept: np.ndarray, v_kept: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
                 scale: float | None = None):
