@@ -3,10 +3,12 @@
 //
 // With one query row per head this is a matrix-vector product per KV head: every K and V row
 // is read once and used for G = Hq/Hkv dot products, so the step is bound by the HBM stream of
-// the two caches and runs on the plain vector ALU (no MFMA: a G-row operand would leave the
-// matrix pipe 3/4 empty and its operand layout would force V through a transpose).
+// the two caches; what matters is that the arithmetic per row stays well below the memory rate.
 //
-//   partial kernel  grid (splits, B*Hkv): a workgroup walks one key range of one KV head.  A
+//   partial kernel  grid (splits, B*Hkv): a workgroup walks one key range of one KV head.
+//                   fp32 inputs: everything on the vector ALU, as follows.  bf16 inputs: the
+//                   scores come from the matrix pipe (decode_partial_mfma_kernel below), the
+//                   value side keeps this layout.  A
 //                   16-byte piece of a row per lane, so D*esize/16 lanes cover a row and a wave
 //                   load instruction reads 64/that many consecutive rows (fully coalesced).  Each
 //                   lane group keeps its own online-softmax state (running max, sum, output
@@ -69,6 +71,32 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&o)[E], f
 // Partial result of one (row of the grid, split): per query head g, D output channels then m, l.
 __device__ __forceinline__ int64_t part_offset(const DecodeShape &s, int bh, int split, int g) {
   return (((int64_t)bh * s.n_splits + split) * s.G + g) * (s.d + 2);
+}
+
+// Merge the per-wave states in LDS ([wave][head][D outputs, m, l]) and store the workgroup's
+// partial result: one thread per (head, channel); the statistics are recomputed per thread.
+template <int D, int G>
+__device__ __forceinline__ void merge_waves_and_store(const DecodeShape &s, float (&wave_state)[DEC_WAVES][G][D + 2],
+                                                      int bh, int split, float *__restrict__ part) {
+  __syncthreads();
+  for (int i = threadIdx.x; i < G * D; i += DEC_THREADS) {
+    const int g = i / D, c = i % D;
+    float mm = wave_state[0][g][D];
+#pragma unroll
+    for (int w = 1; w < DEC_WAVES; ++w) mm = fmaxf(mm, wave_state[w][g][D]);
+    float ll = 0.0f, oo = 0.0f;
+    if (mm != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < DEC_WAVES; ++w) {
+        const float a = fast_exp2(wave_state[w][g][D] - mm);
+        ll += wave_state[w][g][D + 1] * a;
+        oo += wave_state[w][g][c] * a;
+      }
+    }
+    float *dst = part + part_offset(s, bh, split, g);
+    dst[c] = oo;
+    if (c == 0) { dst[D] = mm; dst[D + 1] = ll; }
+  }
 }
 
 template <typename T, int D, int G>
@@ -203,26 +231,170 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeShape
       if (piece == 0) { wave_state[wave][g][D] = m[g]; wave_state[wave][g][D + 1] = l[g]; }
     }
   }
-  __syncthreads();
-  // merge the waves: one thread per (head, channel); the statistics are recomputed per thread
-  for (int i = threadIdx.x; i < G * D; i += DEC_THREADS) {
-    const int g = i / D, c = i % D;
-    float mm = wave_state[0][g][D];
-#pragma unroll
-    for (int w = 1; w < DEC_WAVES; ++w) mm = fmaxf(mm, wave_state[w][g][D]);
-    float ll = 0.0f, oo = 0.0f;
-    if (mm != -INFINITY) {
-#pragma unroll
-      for (int w = 0; w < DEC_WAVES; ++w) {
-        const float a = fast_exp2(wave_state[w][g][D] - mm);
-        ll += wave_state[w][g][D + 1] * a;
-        oo += wave_state[w][g][c] * a;
-      }
-    }
-    float *dst = part + part_offset(s, bh, split, g);
-    dst[c] = oo;
-    if (c == 0) { dst[D] = mm; dst[D + 1] = ll; }
+  merge_waves_and_store<D, G>(s, wave_state, bh, split, part);
+}
+
+// ---- bf16: scores on the matrix pipe ---------------------------------------------------------
+// The G query rows (padded to 16) are the B operand of v_mfma_f32_16x16x32_bf16 and 16 cache rows
+// the A operand, loaded in operand layout as in the score kernels, so a block of 16 rows costs
+// D/32 MFMAs instead of 16 * G dot-product reductions, and each lane takes the exponent of 4
+// scores instead of G per row.  The probabilities go through a small per-wave LDS tile to the
+// value side, which keeps the row-piece layout above (V is contracted over rows, the wrong way
+// round for an MFMA operand).  Every lane of a wave uses the same running maximum per head, so
+// the lane groups' outputs simply add up at the end.
+template <int D, int G>
+__global__ __launch_bounds__(DEC_THREADS) void decode_partial_mfma_kernel(
+    DecodeShape s, const uint16_t *__restrict__ q_new, const uint16_t *__restrict__ k_new,
+    const uint16_t *__restrict__ v_new, uint16_t *k_cache, uint16_t *v_cache, const int32_t *__restrict__ n_valid,
+    float *__restrict__ part) {
+  constexpr int E = 8;
+  constexpr int LPK = D / E;                 // lanes per row (value side)
+  constexpr int KPT = 64 / LPK;              // rows per wave load instruction (value side)
+  constexpr int VT = 16 / KPT;               // value loads per block of 16 rows
+  constexpr int KS = D / 32;                 // MFMA steps over the channels
+  constexpr int GP = G <= 4 ? 4 : 8;         // heads padded to whole float4s in LDS
+  __shared__ float wave_state[DEC_WAVES][G][D + 2];
+  __shared__ __attribute__((aligned(16))) float p_s[DEC_WAVES][16][GP];     // probabilities of the wave's block, [row][head]
+  __shared__ __attribute__((aligned(16))) float corr_s[DEC_WAVES][GP];      // rescale factor of the outputs, per head
+
+  const int bh = blockIdx.y, b = bh / s.Hkv, h = bh % s.Hkv, split = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, quad = lane >> 4;            // score side: head, 4 rows
+  const int slot = lane / LPK, piece = lane % LPK;        // value side: row of the tile, 16-byte piece
+  const int n = n_valid[bh];
+  const bool usable = n >= 0 && n < s.capacity;
+  const int n_total = usable ? n + 1 : 0;
+
+  uint16_t *kc = k_cache + (int64_t)b * s.sb + (int64_t)h * s.sh;
+  uint16_t *vc = v_cache + (int64_t)b * s.sb + (int64_t)h * s.sh;
+  const uint16_t *kn = k_new + ((int64_t)b * s.Hkv + h) * D;
+  const uint16_t *vn = v_new + ((int64_t)b * s.Hkv + h) * D;
+
+  if (split == 0 && usable && threadIdx.x < 2 * LPK) {     // append (see the kernel above)
+    const int pc = threadIdx.x % LPK;
+    if (threadIdx.x < LPK) *(uint4 *)(kc + (int64_t)n * s.st + pc * E) = *(const uint4 *)(kn + pc * E);
+    else *(uint4 *)(vc + (int64_t)n * s.st + pc * E) = *(const uint4 *)(vn + pc * E);
   }
+
+  // query rows as B fragments: lane (head col, quad) holds channels 32*ks + 8*quad .. +7; heads >= G are zero
+  bf16x8 qb[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (col < G) v = *(const uint4 *)(q_new + ((int64_t)b * s.Hq + (int64_t)h * G + col) * D + ks * 32 + quad * 8);
+    qb[ks] = *(const bf16x8 *)&v;
+  }
+
+  float m = -INFINITY, l = 0.0f;             // of head `col` (lanes with col < G), l over this lane's rows only
+  float o[G][E];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int c = 0; c < E; ++c) o[g][c] = 0.0f;
+
+  const int c0 = split * s.chunk, cend = min(c0 + s.chunk, n_total);
+  auto k_ptr = [&](int j, int ks) -> const uint4 * {      // rows below n live in the cache, the rest is the new row
+    return (const uint4 *)((j < n ? kc + (int64_t)j * s.st : kn) + ks * 32 + quad * 8);
+  };
+  auto v_ptr = [&](int j) -> const uint4 * {
+    return (const uint4 *)((j < n ? vc + (int64_t)j * s.st : vn) + piece * E);
+  };
+  uint4 kr[KS], vr[VT];
+  auto load_block = [&](int blk) {
+    const int r0 = c0 + blk * 16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kr[ks] = *k_ptr(r0 + col, ks);
+#pragma unroll
+    for (int t = 0; t < VT; ++t) vr[t] = *v_ptr(r0 + t * KPT + slot);
+  };
+  int blk = wave;
+  if (c0 < cend) load_block(blk);
+  for (; c0 + blk * 16 < cend; blk += DEC_WAVES) {
+    uint4 kcur[KS], vcur[VT];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kcur[ks] = kr[ks];
+#pragma unroll
+    for (int t = 0; t < VT; ++t) vcur[t] = vr[t];
+    load_block(blk + DEC_WAVES);               // next block (addresses clamp to the new row past the end)
+
+    // scores of 16 rows x 16 (padded) heads
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8 *)&kcur[ks], qb[ks], acc, 0, 0, 0);
+    const int r0 = c0 + blk * 16;
+    float sc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sc[e] = r0 + quad * 4 + e < cend ? acc[e] * s.c1 : -INFINITY;
+    float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));          // the same in the 4 lanes of a head
+    const float mn = fmaxf(m, bm);
+    float corr = 1.0f, pr[4] = {0.f, 0.f, 0.f, 0.f};
+    if (mn != -INFINITY) {
+      corr = fast_exp2(m - mn);                  // m = -inf: 0
+      m = mn;
+      float ps = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { pr[e] = fast_exp2(sc[e] - mn); ps += pr[e]; }
+      l = l * corr + ps;
+    }
+    if (col < G) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) p_s[wave][quad * 4 + e][col] = pr[e];
+      if (quad == 0) corr_s[wave][col] = corr;
+    }
+    // the wave's own LDS writes above are read back below: LDS serves a wave's requests in order
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+
+    float cr[GP];
+#pragma unroll
+    for (int i = 0; i < GP; i += 4) *(float4 *)&cr[i] = *(const float4 *)&corr_s[wave][i];
+    bool rescale = false;
+#pragma unroll
+    for (int g = 0; g < G; ++g) rescale |= cr[g] != 1.0f;
+    if (__any(rescale)) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < E; ++c) o[g][c] *= cr[g];
+    }
+#pragma unroll
+    for (int t = 0; t < VT; ++t) {
+      float pg[GP], vf[E];
+#pragma unroll
+      for (int i = 0; i < GP; i += 4) *(float4 *)&pg[i] = *(const float4 *)&p_s[wave][t * KPT + slot][i];
+      Piece<uint16_t>::unpack(vcur[t], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < E; ++c) o[g][c] = fmaf(pg[g], vf[c], o[g][c]);
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // the wave's totals: outputs over the lane groups (lanes with equal piece), l over the 4 lanes of a head
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int c = 0; c < E; ++c) {
+      float x = o[g][c];
+#pragma unroll
+      for (int off = LPK; off < 64; off <<= 1) x += __shfl_xor(x, off);
+      o[g][c] = x;
+    }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (slot == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int c = 0; c < E; ++c) wave_state[wave][g][piece * E + c] = o[g][c];
+  }
+  if (lane < G) { wave_state[wave][lane][D] = m; wave_state[wave][lane][D + 1] = l; }    // lane = head (quad 0)
+  merge_waves_and_store<D, G>(s, wave_state, bh, split, part);
 }
 
 constexpr int DEC_MAX_SPLITS = 64;
@@ -274,15 +446,23 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_combine_kernel(DecodeShape
   }
 }
 
+template <typename T, int D, int G>
+static void launch_partial_g(const DecodeShape &s, dim3 grid, const void *q, const void *kn, const void *vn, void *kc,
+                             void *vc, const int32_t *n_valid, float *part, hipStream_t stream) {
+  if constexpr (sizeof(T) == 2)     // bf16: scores on the matrix pipe
+    hipLaunchKernelGGL((decode_partial_mfma_kernel<D, G>), grid, dim3(DEC_THREADS), 0, stream, s, (const uint16_t *)q,
+                       (const uint16_t *)kn, (const uint16_t *)vn, (uint16_t *)kc, (uint16_t *)vc, n_valid, part);
+  else
+    hipLaunchKernelGGL((decode_partial_kernel<T, D, G>), grid, dim3(DEC_THREADS), 0, stream, s, (const T *)q,
+                       (const T *)kn, (const T *)vn, (T *)kc, (T *)vc, n_valid, part);
+}
+
 template <typename T, int D>
 static hipError_t launch_partial(const DecodeShape &s, const void *q, const void *kn, const void *vn, void *kc,
                                  void *vc, const int32_t *n_valid, float *part, hipStream_t stream) {
-  dim3 grid(s.n_splits, s.B * s.Hkv), block(DEC_THREADS);
-#define WKV_DEC_CASE(GG)                                                                                          \
-  case GG:                                                                                                        \
-    hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), grid, block, 0, stream, s, (const T *)q, (const T *)kn, \
-                       (const T *)vn, (T *)kc, (T *)vc, n_valid, part);                                           \
-    break;
+  dim3 grid(s.n_splits, s.B * s.Hkv);
+#define WKV_DEC_CASE(GG) \
+  case GG: launch_partial_g<T, D, GG>(s, grid, q, kn, vn, kc, vc, n_valid, part, stream); break;
   switch (s.G) {
     WKV_DEC_CASE(1) WKV_DEC_CASE(2) WKV_DEC_CASE(3) WKV_DEC_CASE(4) WKV_DEC_CASE(5) WKV_DEC_CASE(6)
     WKV_DEC_CASE(7) WKV_DEC_CASE(8)
