@@ -59,7 +59,7 @@ wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *
   GroupPtrs gp;
   std::memset(&gp, 0, sizeof(gp));
   gp.q[0] = q_obs; gp.k[0] = k_first; gp.lse[0] = lse_obs;
-  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, lse_obs != nullptr, ws.partials, ws.lse, t_out,
+  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, lse_obs != nullptr, ws.partials, ws.lse, t_out, nullptr,
                               (hipStream_t)hip_stream);
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_score launch");
 }
@@ -81,7 +81,9 @@ wkv_status wkv_topk_windows(const wkv_problem *problem, const float *s, int32_t 
   if (!s || !win_idx_out || !tok_idx_out || !n_keep_out) {
     set_error("s / win_idx_out / tok_idx_out / n_keep_out is NULL"); return WKV_ERR_INVALID_ARG;
   }
-  hipError_t e = launch_topk(pr.shape, pr.bp, 1, s, win_idx_out, tok_idx_out, n_keep_out, (hipStream_t)hip_stream);
+  GroupK gk;
+  std::memset(&gk, 0, sizeof(gk));
+  hipError_t e = launch_topk(pr.shape, pr.bp, gk, 1, s, win_idx_out, tok_idx_out, n_keep_out, (hipStream_t)hip_stream);
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_topk_windows launch");
 }
 
@@ -184,12 +186,16 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
   hipError_t e;
 #define WKV_MARK(i) if (ev && (e = hipEventRecord(ev[i], stream)) != hipSuccess) return hip_fail(e, "event record");
   WKV_MARK(0)
-  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, lse_obs_groups != nullptr, ws.partials, ws.lse, ws.t, stream,
-                   ev ? ev[1] : nullptr);
+  // With window sizes that divide the chunk length the score kernel pools its own windows
+  // (Eq. 3-4 on the scores still in LDS) and only the window scores reach memory.
+  float *s_pool = pl.pool_in_pass2 ? ws.s : nullptr;
+  e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, lse_obs_groups != nullptr, ws.partials, ws.lse, ws.t, s_pool,
+                   stream, ev ? ev[1] : nullptr);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
-  WKV_MARK(3)     // pooling runs inside the selection kernel here: its own slot stays empty
-  e = launch_select(pr.shape, pr.bp, gk, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
+  WKV_MARK(3)     // pooling runs inside the score or the selection kernel here: its own slot stays empty
+  if (s_pool) e = launch_topk(pr.shape, pr.bp, gk, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
+  else e = launch_select(pr.shape, pr.bp, gk, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "select launch");
   WKV_MARK(4)
   e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);

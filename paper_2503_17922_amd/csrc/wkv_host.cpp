@@ -159,6 +159,9 @@ ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   // every pass-2 workgroup re-reads rows * n_chunks1 partials when it folds them itself: worth
   // it (one launch less) only while that stays a few KB
   pl.fold_in_pass2 = pl.mfma && pl.n_chunks1 <= 16;
+  // chunks are multiples of 128 keys: windows never straddle two workgroups when win divides 128
+  pl.pool_in_pass2 = pl.mfma;
+  for (int32_t b = 0; b < s.B; ++b) pl.pool_in_pass2 = pl.pool_in_pass2 && (128 % bp.seq[b].win == 0);
   return pl;
 }
 

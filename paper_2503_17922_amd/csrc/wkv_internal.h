@@ -67,6 +67,7 @@ struct ScorePlan {
   int32_t m_pad;               // rows padded to a multiple of 16
   bool mfma;                   // bf16 MFMA kernels (else the generic ones)
   bool fold_in_pass2;          // MFMA path: pass 2 folds the pass-1 partials itself (few chunks per row)
+  bool pool_in_pass2;          // MFMA path: pass 2 can pool its chunk's windows (every window size divides 128)
 };
 
 struct Workspace {
@@ -89,10 +90,10 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_group
 // `mid`, if not null, is recorded between the stats pass and the score pass.
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &plan,
                         const GroupPtrs &gp, int32_t n_groups, bool have_lse, float2 *partials, float *lse,
-                        float *t_out, hipStream_t stream, hipEvent_t mid = nullptr);
+                        float *t_out, float *s_pool, hipStream_t stream, hipEvent_t mid = nullptr);
 hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
                        float *s_out, hipStream_t stream);
-hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
+hipError_t launch_topk(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *sc,
                        int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream);
 // Pooling and selection in one launch (same results as launch_pool followed by launch_topk).
 hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *t,

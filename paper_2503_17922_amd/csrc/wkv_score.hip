@@ -24,6 +24,7 @@
 //   * generic (fp32 inputs, or M > 128): plain fp32 FMAs, thread-per-row for the stats,
 //     thread-per-key for the scores, the other operand broadcast from LDS.
 #include "wkv_device.h"
+#include "wkv_pool.h"
 
 namespace wkv {
 
@@ -198,7 +199,8 @@ template <int D, int MT, int PASS>
 __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    const float *__restrict__ lse_g,
-                                                                   float *__restrict__ t_out) {
+                                                                   float *__restrict__ t_out,
+                                                                   float *__restrict__ s_pool) {
   constexpr int KS = D / 32;
   constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
   __shared__ uint4 qfrag[MT * KS * 64];
@@ -206,7 +208,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   // Pass 2 collects the chunk's token scores here and writes them out once at the end: global
   // stores inside the loop would share the vector-memory counter with the key prefetch and make
   // every wait for keys also wait for store acknowledgements.
-  __shared__ float t_s[PASS == 2 ? MAX_CHUNK2 + 256 : 1];
+  __shared__ __attribute__((aligned(16))) float t_s[PASS == 2 ? MAX_CHUNK2 + 256 : 1];
   __shared__ float lse_s[PASS == 2 ? MT * 16 : 1];
 
   // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
@@ -229,7 +231,8 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   if (PASS == 2) {
     const int cend_fill = min(c0 + chunk, s.t_stride);
     if (c0 >= n_review) {
-      for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
+      if (!s_pool)
+        for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
       return;
     }
   }
@@ -402,8 +405,18 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
 
   if (PASS == 2) {
     __syncthreads();
-    const int cend_fill = min(c0 + chunk, s.t_stride);
-    for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
+    if (s_pool) {
+      // Eq. 3-4 on the chunk's token scores while they are in LDS: the chunk starts on a window
+      // boundary and no window but the sequence's last (partial) one ends outside it
+      const SeqParam sp = bp.seq[b];
+      const int w0 = c0 / sp.win, w1 = (cend + sp.win - 1) / sp.win;
+      float *srow = s_pool + row * s.nw_max;
+      for (int w = w0 + threadIdx.x; w < w1; w += MF_THREADS)
+        srow[w] = pool_window(t_s - c0, w, sp.win, n_review, sp.p);
+    } else {
+      const int cend_fill = min(c0 + chunk, s.t_stride);
+      for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
+    }
   }
   if (PASS == 1) {
     // merge the 4 quads of each row (lanes col, col+16, col+32, col+48), then the 4 waves
@@ -432,7 +445,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
 template <int D, int MT>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                               int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
-                              hipStream_t stream, hipEvent_t mid) {
+                              float *s_pool, hipStream_t stream, hipEvent_t mid) {
   dim3 block(MF_THREADS);
   hipError_t e;
   if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
@@ -440,7 +453,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
     if (s.t_stride <= 0) return hipSuccess;
   } else {
     dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-    hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
@@ -452,7 +465,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
   ScorePlan pl2 = pl;
   if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
   return hipGetLastError();
 }
 
@@ -488,12 +501,12 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
 }
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
-                        int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
+                        int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out, float *s_pool,
                         hipStream_t stream, hipEvent_t mid) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
 #define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
+  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
     WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
     WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
 #undef WKV_MFMA_CASE

@@ -4,90 +4,11 @@
 // 1/64 of the bytes of the key stream that produced it, so they are latency bound rather than
 // bandwidth bound: the design goal is few launches and no serial host involvement.
 #include "wkv_internal.h"
+#include "wkv_pool.h"
 
 namespace wkv {
 
 constexpr int POOL_THREADS = 256;
-
-// ------------------------------------------------------------------------------------------
-// Eq. 3-4: s_w = sum(Top-p(W_w)) / min(p, win), one thread per window.
-// Register-resident pooling for the common window sizes.  The window's token scores sit in
-// registers (loaded as float4s: a lane reads its window's 4*WIN contiguous bytes) and are put
-// in descending order by a fully unrolled bitonic network (min/max pairs, nothing indexed
-// dynamically); the score is the sum of the first p.  Which of several equal values counts
-// as "in the top p" does not change that sum.
-// ------------------------------------------------------------------------------------------
-template <int WIN>
-__device__ __forceinline__ float pool_window_regs(const float *__restrict__ trow, int w, int n_review, int p) {
-  float v[WIN];
-  const int tok0 = w * WIN;
-  const int size = min(WIN, n_review - tok0);
-  if (size == WIN && ((uintptr_t)(trow + tok0) & 15) == 0) {
-#pragma unroll
-    for (int i = 0; i < WIN; i += 4) {
-      const float4 q = *(const float4 *)(trow + tok0 + i);
-      v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < WIN; ++i) v[i] = i < size ? trow[tok0 + i] : -INFINITY;
-  }
-  float acc = 0.0f;
-  if (p >= size) {
-#pragma unroll
-    for (int i = 0; i < WIN; ++i) acc += i < size ? v[i] : 0.0f;
-  } else {
-#pragma unroll
-    for (int k = 2; k <= WIN; k <<= 1)
-#pragma unroll
-      for (int j = k >> 1; j > 0; j >>= 1)
-#pragma unroll
-        for (int i = 0; i < WIN; ++i) {
-          const int l = i ^ j;
-          if (l > i) {
-            const float lo = fminf(v[i], v[l]), hi = fmaxf(v[i], v[l]);
-            const bool descending = (i & k) == 0;
-            v[i] = descending ? hi : lo;
-            v[l] = descending ? lo : hi;
-          }
-        }
-#pragma unroll
-    for (int i = 0; i < WIN; ++i) acc += i < p ? v[i] : 0.0f;     // p < size: none of these is padding
-  }
-  return acc / (float)p;
-}
-
-// Any window size: plain loops over global memory (cached; O(size^2) compares).  Element i is
-// kept when fewer than p elements are larger, equal values ordered by position.
-__device__ __forceinline__ float pool_window_any(const float *__restrict__ trow, int w, int win, int n_review, int p) {
-  const int tok0 = w * win;
-  const int size = min(win, n_review - tok0);
-  float acc = 0.0f;
-  if (p >= size) {
-    for (int i = 0; i < size; ++i) acc += trow[tok0 + i];
-  } else {
-    for (int i = 0; i < size; ++i) {
-      const float vi = trow[tok0 + i];
-      int rank = 0;
-      for (int j = 0; j < size; ++j) {
-        const float vj = trow[tok0 + j];
-        rank += (vj > vi) || (vj == vi && j < i);
-      }
-      if (rank < p) acc += vi;
-    }
-  }
-  return acc / (float)p;
-}
-
-// Window score by whichever of the two fits the window size (uniform per workgroup).
-__device__ __forceinline__ float pool_window(const float *__restrict__ trow, int w, int win, int n_review, int p) {
-  switch (win) {
-    case 8: return pool_window_regs<8>(trow, w, n_review, p);
-    case 16: return pool_window_regs<16>(trow, w, n_review, p);
-    case 32: return pool_window_regs<32>(trow, w, n_review, p);
-    default: return pool_window_any(trow, w, win, n_review, p);
-  }
-}
 
 // One thread per window.
 __global__ __launch_bounds__(POOL_THREADS) void pool_kernel(Shape s, BatchParams bp, const float *__restrict__ t,
@@ -246,13 +167,15 @@ __device__ __forceinline__ void topk_body(const Shape &s, const SeqParam sp, uin
   if (tid == 0) n_keep[row] = nk;
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams bp, const float *__restrict__ sc,
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(Shape s, BatchParams bp, GroupK gk,
+                                                            const float *__restrict__ sc,
                                                             int32_t *__restrict__ win_idx,
                                                             int32_t *__restrict__ tok_idx,
                                                             int32_t *__restrict__ n_keep) {
   extern __shared__ uint32_t keys[];            // [nw_max], later reused for the selected list
   const int bh = blockIdx.x, b = bh / s.Hkv, g = blockIdx.y;
-  const SeqParam sp = bp.seq[b];
+  SeqParam sp = bp.seq[b];
+  if (gk.in_use) sp.k = gk.k[g * s.B + b];      // the group's own budget
   const int nw = (sp.L - s.w_obs + sp.win - 1) / sp.win;
   const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
   const float *srow = sc + row * s.nw_max;
@@ -280,7 +203,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void select_kernel(Shape s, BatchPara
   topk_body(s, sp, keys, row, win_idx, tok_idx, n_keep);
 }
 
-hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *sc,
+hipError_t launch_topk(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *sc,
                        int32_t *win_idx, int32_t *tok_idx, int32_t *n_keep, hipStream_t stream) {
   const size_t lds = (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(uint32_t);
   if (lds > 48 * 1024) {     // beyond the default dynamic-LDS limit: raise it (per device, any thread)
@@ -289,7 +212,7 @@ hipError_t launch_topk(const Shape &s, const BatchParams &bp, int32_t n_groups, 
     if (e != hipSuccess) return e;
   }
   dim3 grid(s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL(topk_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, sc, win_idx, tok_idx, n_keep);
+  hipLaunchKernelGGL(topk_kernel, grid, dim3(TOPK_THREADS), lds, stream, s, bp, gk, sc, win_idx, tok_idx, n_keep);
   return hipGetLastError();
 }
 
