@@ -127,6 +127,18 @@ def test_config_c5_batched_mixed(device):
     run_and_check(w, device, n_oracle=32, n_gather_cpu=16, check_stage_group=5)
 
 
+def test_longest_supported_window_count(device):
+    # 32768 windows per sequence (the library's limit) = a 262 176-token prefix at window size 8:
+    # 128 KB of selection keys in LDS, 94 key chunks per row in the score passes
+    w = S.Workload(name="long", seed=1006, dtype="bf16", n_groups=1, gamma=1, n_q_heads=32, n_kv_heads=8, head_dim=128,
+                   w_obs=32, seq_len=[8 * 32768 + 32], win=[8], top_p=[8], k_windows=[3000])
+    assert W.wkv_get_dims(P.make_problem(w)).nw_max == W.WKV_MAX_WINDOWS
+    run_and_check(w, device, n_oracle=2, n_gather_cpu=4)
+    with pytest.raises(W.WkvError) as e:                 # one window more is refused on the host
+        W.wkv_get_dims(P.make_problem(S.scaled_workload(w, seq_len=[8 * 32768 + 33])))
+    assert e.value.status == W.WKV_ERR_UNSUPPORTED
+
+
 # ---------------------------------------------------------------------------------------
 # edge cases
 # ---------------------------------------------------------------------------------------
