@@ -30,11 +30,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # what the same counter reads for a plain 256 MiB device copy (2.0 and 1.0 on this machine); the
 # runs are summarised in profiles/compress_groups_c4.md.  Missing key = not measured (null).
 MEASURED_TRAFFIC_BYTES = {
-    ("c4", "score_pre"): 557.3e6,      # statistics pass
-    ("c4", "score"): 567.9e6,          # score pass (folds the statistics itself)
-    ("c4", "topk_windows"): 9.7e6,     # pooling + selection
+    ("c4", "score_pre"): 557.4e6,      # statistics pass
+    ("c4", "score"): 560.2e6,          # score pass (folds the statistics, pools its windows)
+    ("c4", "topk_windows"): 1.8e6,     # selection on the window scores
     ("c4", "gather"): 1083.2e6,
-    ("c4", "pipeline"): 2218.1e6,
+    ("c4", "pipeline"): 2202.6e6,
 }
 
 
