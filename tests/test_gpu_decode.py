@@ -112,3 +112,29 @@ def test_decode_full_cache_is_refused_per_row(device):
     assert bool(torch.isnan(out[0]).all()) and not bool(torch.isnan(out[1]).any())
     assert torch.equal(n_valid[0], before_n[0]) and torch.equal(n_valid[1], before_n[1] + 1)
     assert torch.equal(st.k_out[0][0], before_k[0])
+
+
+def test_decode_strided_cache_and_explicit_scale(device):
+    # token-major caches [B, capacity, Hkv, d] and a caller-chosen logit scale; hand-made rows, no compression
+    rng_seed, B, H, G, d, cap = 94, 2, 3, 2, 64, 300
+    w = S.Workload(name="dec_strided", seed=rng_seed, dtype="bf16", n_groups=1, gamma=1, n_q_heads=H * G, n_kv_heads=H,
+                   head_dim=d, w_obs=4, seq_len=[64], win=[8], top_p=[8], k_windows=[1])     # only the generator's seed and dtype are used
+    kc = _new_token(w, device, 100, 0, (B, cap, H, d)); vc = _new_token(w, device, 100, 1, (B, cap, H, d))
+    n0 = torch.tensor([[257, 0, 13], [299, 64, 1]], dtype=torch.int32, device=device)       # includes an empty cache and a nearly full one
+    n_valid = n0.clone()
+    shape = W.DecodeShape(batch=B, n_q_heads=H * G, n_kv_heads=H, head_dim=d, capacity=cap, dtype=W.WKV_BF16, scale=0.37,
+                          cache_strides=(cap * H * d, d, H * d))
+    ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    out = torch.empty((B, H * G, d), dtype=torch.float32, device=device)
+    q = _new_token(w, device, 101, 0, (B, H * G, d)); kn = _new_token(w, device, 101, 1, (B, H, d)); vn = _new_token(w, device, 101, 2, (B, H, d))
+    k_before, v_before = kc.clone(), vc.clone()
+    W.wkv_decode_step(shape, q, kn, vn, kc, vc, n_valid, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(n_valid, n0 + 1)
+    for b, h in itertools.product(range(B), range(H)):
+        n = int(n0[b, h])
+        want, _, _ = O.decode_step(P.host_f64(w, q[b, h * G:(h + 1) * G]), P.host_f64(w, k_before[b, :n, h]),
+                                   P.host_f64(w, v_before[b, :n, h]), P.host_f64(w, kn[b, h]), P.host_f64(w, vn[b, h]), scale=0.37)
+        np.testing.assert_allclose(out[b, h * G:(h + 1) * G].cpu().numpy(), want, rtol=RTOL, atol=ATOL, err_msg=f"b{b} h{h}")
+        k_before[b, n, h] = kn[b, h]; v_before[b, n, h] = vn[b, h]
+    assert torch.equal(k_before, kc) and torch.equal(v_before, vc)
