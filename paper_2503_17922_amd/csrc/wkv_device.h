@@ -56,20 +56,33 @@ constexpr float MF_BIG = 1.0e30f;        // a tile sum above this re-references 
 // Arrange the M query rows of KV head h as MFMA B fragments in LDS.
 // Fragment (mt, ks) is 64 x 16 bytes: lane l holds row 16*mt + l%16, channels 32*ks + 8*(l/16)..+7.
 template <int D, int MT>
-__device__ __forceinline__ void stage_q_fragments(const Shape &s, const void *qbase, int b, int h, uint4 *qfrag) {
-  constexpr int KS = D / 32;
-  for (int i = threadIdx.x; i < MT * KS * 64; i += MF_THREADS) {
-    const int l = i & 63, f = i >> 6, ks = f % KS, mt = f / KS;
-    const int r = mt * 16 + (l & 15);
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r < s.M) {
-      const int hq = h * s.G + r / s.w_obs, io = r % s.w_obs;
-      const int64_t off = (int64_t)b * s.q_sb + (int64_t)hq * s.q_sh + (int64_t)io * s.q_st + ks * 32 + (l >> 4) * 8;
-      v = *(const uint4 *)((const uint16_t *)qbase + off);
+struct QStage {
+  static constexpr int KS = D / 32;
+  static constexpr int TOTAL = MT * KS * 64;               // 16-byte pieces of the fragments
+  static constexpr int N = (TOTAL + MF_THREADS - 1) / MF_THREADS;   // per thread
+  uint4 v[N];
+  // Issue every load of this thread at once (independent of each other, so their latencies
+  // overlap; a load-then-store loop would pay one round trip per piece).
+  __device__ __forceinline__ void load(const Shape &s, const void *qbase, int b, int h) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = threadIdx.x + k * MF_THREADS;
+      const int l = i & 63, f = i >> 6, ks = f % KS, mt = f / KS;
+      const int r = mt * 16 + (l & 15);
+      v[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (i < TOTAL && r < s.M) {
+        const int hq = h * s.G + r / s.w_obs, io = r % s.w_obs;
+        const int64_t off = (int64_t)b * s.q_sb + (int64_t)hq * s.q_sh + (int64_t)io * s.q_st + ks * 32 + (l >> 4) * 8;
+        v[k] = *(const uint4 *)((const uint16_t *)qbase + off);
+      }
     }
-    qfrag[i] = v;
   }
-}
+  __device__ __forceinline__ void store(uint4 *qfrag) const {
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+      if (threadIdx.x + k * MF_THREADS < TOTAL) qfrag[threadIdx.x + k * MF_THREADS] = v[k];
+  }
+};
 
 // Sum over the 16 lanes of a DPP row (lanes with equal l/16); every lane gets the total.
 __device__ __forceinline__ float row16_sum(float x) {

@@ -241,10 +241,20 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(-INFINITY, 0.0f);
     return;
   }
+  // Loads that depend on nothing staged below go out first, so that their latencies overlap: the
+  // query fragments of this workgroup and the first key tile of every wave.
+  QStage<D, MT> qstage;
+  qstage.load(s, gp.q[g], b, h);
+  const int cend = min(c0 + chunk, limit);
+  const uint16_t *kbase = (const uint16_t *)gp.k[g] + (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh + quad * 8;
+  int j0 = c0 + wave * STEP;
+  KFrags<KS> ka, kb;
+  load_k<KS>(ka, kbase, s.kv_st, j0, col, max(cend, 1));
+
   if (PASS == 2) {
     // The base-2 log-sum-exp of the MT*16 rows, into LDS.  With few chunks per row the workgroup
-    // folds the (m, z) partials of pass 1 itself (TPR adjacent lanes share a row; the loads
-    // overlap the query staging below); otherwise a fold launch or the caller provided them.
+    // folds the (m, z) partials of pass 1 itself (TPR adjacent lanes share a row; the query
+    // and key loads issued above are in flight meanwhile); otherwise a fold launch or the caller provided them.
     constexpr int TPR = MF_THREADS / (MT * 16);
     const int r = threadIdx.x / TPR, part = threadIdx.x % TPR;
     if (pl.fold_in_pass2) {
@@ -260,7 +270,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       lse_s[r] = row_lse2(s, pl, gp, lse_g, g, b, h, row, r);
     }
   }
-  stage_q_fragments<D, MT>(s, gp.q[g], b, h, qfrag);
+  qstage.store(qfrag);
   __syncthreads();
 
   // per-lane row constants: this lane's query row of row tile mt is 16*mt + col
@@ -272,8 +282,6 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
     zsum[mt] = 0.0f;
   }
 
-  const int cend = min(c0 + chunk, limit);
-  const uint16_t *kbase = (const uint16_t *)gp.k[g] + (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh + quad * 8;
   const float c1 = s.c1;
 
   // One wave iteration: prefetch the keys of the next iteration into `kn`, compute on `kf`.
@@ -392,9 +400,6 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
     }
   };
 
-  int j0 = c0 + wave * STEP;
-  KFrags<KS> ka, kb;
-  load_k<KS>(ka, kbase, s.kv_st, j0, col, max(cend, 1));
   while (j0 < cend) {
     iteration(ka, kb, j0);
     j0 += MF_WAVES * STEP;
