@@ -22,6 +22,9 @@
  *   - Work is enqueued on the caller's hipStream_t (passed as void*; NULL = default stream).
  *     Calls return without synchronising; results are valid in stream order.
  *   - The library allocates nothing, frees nothing and keeps no device state between calls.
+ *     Every call except wkv_compress_groups_profiled is a fixed sequence of kernel launches on
+ *     the stream (no memset or copy nodes, no host synchronisation), so it can be captured into
+ *     a HIP graph; host arrays are read at capture time.
  *   - Every argument is validated on the host before the first launch; a failed validation
  *     launches nothing.  Errors come back as wkv_status; nothing is thrown.
  *   - All index outputs are int32.  Tensors are addressed with 64-bit offsets.

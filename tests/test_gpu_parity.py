@@ -356,3 +356,42 @@ def test_window_pool_alone(device):
         for h in range(2):
             want = O.window_scores(t[0, h].astype(np.float64), win, p)
             np.testing.assert_allclose(s_dev[0, h].cpu().numpy(), want, rtol=2e-6)
+
+
+def test_graph_capture_and_replay(device):
+    # The batched call is plain kernel launches on the caller's stream (no allocation, no host
+    # synchronisation, no memset nodes), so it can be captured into a HIP graph.  Replays with the
+    # inputs changed in place must match eager calls on the same inputs, every time.
+    w = _mini(seq_len=[1500, 700], win=[8, 16], top_p=[8, 5], k_windows=[40, 9], n_groups=2, gamma=2)
+    st = P.DeviceState(w, device)
+    call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, None, st.k, st.v, st.k_out, st.v_out,
+                          st.win_idx, st.tok_idx, st.n_keep, st.workspace)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(side.cuda_stream)                       # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        # new inputs, same buffers: permute the tokens of the scored layers and of one value layer
+        perm = torch.randperm(w.max_seq_len, device=device, generator=torch.Generator(device=device).manual_seed(rep))
+        for g in range(w.n_groups):
+            st.k[g * w.gamma].copy_(st.k[g * w.gamma][:, :, perm])
+        st.v[1].copy_(st.v[1][:, :, perm])
+        for o in st.k_out + st.v_out:
+            o.fill_(3.0)
+        st.tok_idx.fill_(-9); st.win_idx.fill_(-9); st.n_keep.fill_(-9)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out)]
+        for o in st.k_out + st.v_out:
+            o.fill_(5.0)
+        st.tok_idx.fill_(-8); st.win_idx.fill_(-8); st.n_keep.fill_(-8)
+        call()                                       # eager, default stream
+        torch.cuda.synchronize()
+        want = (st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out)
+        for a, b_ in zip(got, want):
+            assert torch.equal(a, b_), f"replay {rep} differs from the eager call"
