@@ -229,6 +229,19 @@ wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
                              double *budgets_out);
 
 /*
+ * Section 3.2 (how alike the selections of different layers are): Jaccard similarity
+ * |A n B| / |A u B| of the retained token positions of every pair of index sets, e.g. of the
+ * layers of a model each selected on its own (wkv_compress_groups with gamma = 1).
+ *   n_sets        1 .. WKV_MAX_GROUPS
+ *   tok_idx       device int32 [n_sets, batch, n_kv_heads, nkeep_max], rows ascending
+ *   n_keep        device int32 [n_sets, batch, n_kv_heads]       (both as written by the
+ *                 selection calls; values outside [0, nkeep_max] are clamped)
+ *   jaccard_out   device float32 [n_sets, n_sets, batch, n_kv_heads]; 1 for two empty sets
+ */
+wkv_status wkv_index_jaccard(const wkv_problem *problem, int32_t n_sets, const int32_t *tok_idx,
+                             const int32_t *n_keep, float *jaccard_out, void *hip_stream);
+
+/*
  * Generation over the compact cache (what the throughput test of Section 3.5 runs): one decode
  * step of one layer.  For every (sequence b, KV head h) with n = n_valid[b,h] retained rows, the
  * new token's key and value rows are appended at row n of the compact caches, and each of the

@@ -218,3 +218,14 @@ def decode_step(q_new: np.ndarray, k_kept: np.ndarray, v_kept: np.ndarray, k_new
         e = np.exp(logits - logits.max())
         out[g] = (e / e.sum()) @ V
     return out, K, V
+
+
+# --------------------------------------------------------------------------------------
+# Section 3.2 — how alike the retained positions of two layers are
+# --------------------------------------------------------------------------------------
+def jaccard(idx_a: Sequence[int], idx_b: Sequence[int]) -> float:
+    """Jaccard similarity |A n B| / |A u B| of two sets of retained token positions (1.0 when
+    both are empty)."""
+    a, b = set(int(x) for x in idx_a), set(int(x) for x in idx_b)
+    union = len(a | b)
+    return 1.0 if union == 0 else len(a & b) / union

@@ -23,7 +23,7 @@ STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
 
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
            "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string",
-           "wkv_last_error", "wkv_decode_workspace_bytes", "wkv_decode_step")
+           "wkv_last_error", "wkv_decode_workspace_bytes", "wkv_decode_step", "wkv_index_jaccard")
 
 
 class WkvError(RuntimeError):
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
     l.wkv_compress_groups_profiled.restype = C.c_int
     l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
     l.wkv_group_budgets.restype = C.c_int
+    l.wkv_index_jaccard.argtypes = [P, C.c_int32, VP, VP, VP, VP]; l.wkv_index_jaccard.restype = C.c_int
     DP = C.POINTER(_DecodeShape)
     l.wkv_decode_workspace_bytes.argtypes = [DP]; l.wkv_decode_workspace_bytes.restype = C.c_size_t
     l.wkv_decode_step.argtypes = [DP, VP, VP, VP, VP, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_decode_step.restype = C.c_int
@@ -220,6 +221,10 @@ def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, 
     is the trailing keyword here: a nested [n_groups][batch] sequence of ints, or None."""
     CompressCall(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, k_layers, v_layers, k_out_layers,
                  v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, k_windows_groups)(stream)
+
+
+def wkv_index_jaccard(problem, n_sets, tok_idx, n_keep, jaccard_out, stream=None) -> None:
+    _check(lib().wkv_index_jaccard(problem.ref(), n_sets, _ptr(tok_idx), _ptr(n_keep), _ptr(jaccard_out), _stream(stream)))
 
 
 class DecodeShape:

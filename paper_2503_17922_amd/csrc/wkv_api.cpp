@@ -249,6 +249,17 @@ wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_gr
   return st;
 }
 
+wkv_status wkv_index_jaccard(const wkv_problem *problem, int32_t n_sets, const int32_t *tok_idx, const int32_t *n_keep,
+                             float *jaccard_out, void *hip_stream) {
+  Prepared pr;
+  wkv_status st = prepare(problem, &pr);
+  if (st != WKV_OK) return st;
+  if (n_sets < 1 || n_sets > WKV_MAX_GROUPS) { set_error("n_sets outside [1, %d]", WKV_MAX_GROUPS); return WKV_ERR_INVALID_ARG; }
+  if (!tok_idx || !n_keep || !jaccard_out) { set_error("tok_idx / n_keep / jaccard_out is NULL"); return WKV_ERR_INVALID_ARG; }
+  hipError_t e = launch_jaccard(pr.shape, n_sets, tok_idx, n_keep, jaccard_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_index_jaccard launch");
+}
+
 wkv_status wkv_decode_step(const wkv_decode_shape *shape, const void *q_new, const void *k_new, const void *v_new,
                            void *k_cache, void *v_cache, int32_t *n_valid, float *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream) {

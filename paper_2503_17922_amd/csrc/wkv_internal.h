@@ -101,6 +101,9 @@ hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk
 hipError_t launch_gather(const Shape &s, const LayerPtrs &lp, int32_t n_layers, int32_t gamma,
                          const int32_t *tok_idx, const int32_t *n_keep, hipStream_t stream);
 
+hipError_t launch_jaccard(const Shape &s, int32_t n_sets, const int32_t *tok_idx, const int32_t *n_keep, float *out,
+                          hipStream_t stream);
+
 // ---- decode over the compact cache --------------------------------------------------------
 struct DecodeShape {
   int32_t B, Hq, Hkv, d, G, dtype;

@@ -229,4 +229,49 @@ hipError_t launch_select(const Shape &s, const BatchParams &bp, const GroupK &gk
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Jaccard similarity of the retained positions of every pair of index sets (Section 3.2).
+// One workgroup per (set i, set j, sequence, KV head): both rows are ascending, so each thread
+// looks its elements of row i up in row j by binary search; |A u B| = |A| + |B| - |A n B|.
+// ------------------------------------------------------------------------------------------
+constexpr int JAC_THREADS = 256;
+
+__global__ __launch_bounds__(JAC_THREADS) void jaccard_kernel(Shape s, int32_t n_sets, const int32_t *__restrict__ tok_idx,
+                                                              const int32_t *__restrict__ n_keep,
+                                                              float *__restrict__ out) {
+  __shared__ int wave_hits[JAC_THREADS / 64];
+  const int bh = blockIdx.x, i = blockIdx.y, j = blockIdx.z;
+  const int64_t rows = (int64_t)s.B * s.Hkv;
+  const int32_t *a = tok_idx + ((int64_t)i * rows + bh) * s.nkeep_max;
+  const int32_t *b = tok_idx + ((int64_t)j * rows + bh) * s.nkeep_max;
+  const int na = min(max(n_keep[(int64_t)i * rows + bh], 0), s.nkeep_max);
+  const int nb = min(max(n_keep[(int64_t)j * rows + bh], 0), s.nkeep_max);
+  int hits = 0;
+  for (int k = threadIdx.x; k < na; k += JAC_THREADS) {
+    const int32_t x = a[k];
+    int lo = 0, hi = nb;                       // first position of row j not below x
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (b[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    hits += lo < nb && b[lo] == x;
+  }
+  for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
+  if ((threadIdx.x & 63) == 0) wave_hits[threadIdx.x >> 6] = hits;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int inter = 0;
+    for (int w = 0; w < JAC_THREADS / 64; ++w) inter += wave_hits[w];
+    const int uni = na + nb - inter;
+    out[((int64_t)i * n_sets + j) * rows + bh] = uni == 0 ? 1.0f : (float)inter / (float)uni;
+  }
+}
+
+hipError_t launch_jaccard(const Shape &s, int32_t n_sets, const int32_t *tok_idx, const int32_t *n_keep, float *out,
+                          hipStream_t stream) {
+  dim3 grid(s.B * s.Hkv, n_sets, n_sets);
+  hipLaunchKernelGGL(jaccard_kernel, grid, dim3(JAC_THREADS), 0, stream, s, n_sets, tok_idx, n_keep, out);
+  return hipGetLastError();
+}
+
 }  // namespace wkv

@@ -395,3 +395,32 @@ def test_graph_capture_and_replay(device):
         want = (st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out)
         for a, b_ in zip(got, want):
             assert torch.equal(a, b_), f"replay {rep} differs from the eager call"
+
+
+def test_per_layer_selection_and_index_similarity(device):
+    # Section 3.2: every layer selects on its own (gamma = 1); the Jaccard similarity of the retained
+    # positions of every pair of layers.  Layers 1..3 are made to resemble layer 0 to different
+    # degrees (a mix of its keys and queries with their own: plain tensor arithmetic on the inputs).
+    n_layers = 4
+    w = _mini(seq_len=[2000, 900], win=[8, 16], top_p=[8, 5], k_windows=[30, 10], n_groups=n_layers, gamma=1)
+    st = P.DeviceState(w, device)
+    for l, rho in ((1, 0.95), (2, 0.7), (3, 0.0)):
+        a, b_ = rho, (1.0 - rho * rho) ** 0.5
+        st.k[l].copy_((a * st.k[0].float() + b_ * st.k[l].float()).to(st.k[l].dtype))
+        st.q[l].copy_((a * st.q[0].float() + b_ * st.q[l].float()).to(st.q[l].dtype))
+    st.compress()
+    B, H = w.batch, w.n_kv_heads
+    out = torch.full((n_layers, n_layers, B, H), -1.0, dtype=torch.float32, device=device)
+    W.wkv_index_jaccard(st.problem, n_layers, st.tok_idx, st.n_keep, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    tok = st.tok_idx.cpu().numpy(); nk = st.n_keep.cpu().numpy()
+    for i, j, b, h in itertools.product(range(n_layers), range(n_layers), range(B), range(H)):
+        want = O.jaccard(tok[i, b, h, : nk[i, b, h]], tok[j, b, h, : nk[j, b, h]])
+        assert got[i, j, b, h] == pytest.approx(want, rel=1e-6), f"jaccard layers {i},{j} b{b} h{h}"
+    # every layer's own selection is what the oracle selects for that layer alone
+    for l, b, h in itertools.product(range(n_layers), range(B), range(H)):
+        t, s, sel, idx = P.oracle_problem(w, st.q[l], st.k[l], b, h)
+        P.check_selection(s, sel, st.win_idx.cpu().numpy()[l, b, h, : w.k_windows[b]], w.k_windows[b], f"layer {l} b{b} h{h}")
+    mean = got.mean(axis=(2, 3))
+    assert np.allclose(np.diag(mean), 1.0) and mean[0, 1] > mean[0, 2] > mean[0, 3], f"similarity should fall with the mixing weight: {mean[0]}"

@@ -328,6 +328,21 @@ def test_decode_step_closed_forms():
     np.testing.assert_allclose(out[0], vv[4], atol=1e-9)
 
 
+def test_jaccard_closed_forms_and_numpy():
+    assert O.jaccard([], []) == 1.0
+    assert O.jaccard([1, 2, 3], [1, 2, 3]) == 1.0
+    assert O.jaccard([1, 2, 3], [4, 5]) == 0.0
+    assert O.jaccard(range(0, 8), range(4, 12)) == pytest.approx(4 / 12)          # half of each shared
+    rng = np.random.default_rng(31)
+    for _ in range(20):
+        a = np.unique(rng.integers(0, 200, size=rng.integers(0, 80)))
+        b = np.unique(rng.integers(0, 200, size=rng.integers(0, 80)))
+        inter, union = len(np.intersect1d(a, b)), len(np.union1d(a, b))
+        want = 1.0 if union == 0 else inter / union
+        assert O.jaccard(a, b) == pytest.approx(want, rel=1e-15)
+        assert O.jaccard(a, b) == O.jaccard(b, a)
+
+
 @pytest.mark.parametrize("H,lam,total", [(4, 14, 8192.0), (8, 14, 4096.0 * 8), (7, 3, 1000.0)])
 def test_group_budgets_closed_forms(H, lam, total):
     b = O.group_budgets(total, H, lam)
