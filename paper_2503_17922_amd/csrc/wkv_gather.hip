@@ -13,7 +13,7 @@
 namespace wkv {
 
 constexpr int GATHER_THREADS = 256;
-constexpr int GATHER_UNROLL = 4;
+constexpr int GATHER_UNROLL = 2;   // measured on MI355X: 2 rows in flight per lane beat 1, 3, 4, 8 and 16
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int LPR>  // lanes per row
