@@ -263,6 +263,29 @@ def test_lse_handoff_small_configs(device):
     _check_lse_handoff(w, device, groups_oracle=[0, 1])                           # ragged batch, two groups
 
 
+def test_lse_handoff_full_model(device):
+    # the 32K configuration with the oracle's normalisers handed over for all 8 groups: the
+    # selections must be the oracle's (near-ties aside) and the gather exact for what was selected
+    w = S.make_workload("c4")
+    st = P.DeviceState(w, device)
+    lse = [st.oracle_lse(g) for g in range(w.n_groups)]
+    st.compress(lse=lse)
+    win = st.win_idx.cpu().numpy(); tok = st.tok_idx.cpu().numpy(); nkeep = st.n_keep.cpu().numpy()
+    problems = _sample(itertools.product(range(w.n_groups), range(w.batch), range(w.n_kv_heads)), 12, 3)
+    for g, b, h in itertools.product(range(w.n_groups), range(w.batch), range(w.n_kv_heads)):
+        P.check_indices_structure(w, b, win[g, b, h], tok[g, b, h], int(nkeep[g, b, h]), st.dims.k_max, st.dims.nkeep_max,
+                                  f"c4 lse g{g} b{b} h{h}")
+    for g, b, h in problems:
+        t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
+        if P.check_selection(s, sel, win[g, b, h, : w.k_windows[b]], w.k_windows[b], f"c4 lse g{g} b{b} h{h}"):
+            assert np.array_equal(tok[g, b, h, : len(idx)], idx)
+        rows = torch.from_numpy(tok[g, b, h, : nkeep[g, b, h]].astype(np.int64)).to(device)
+        for l in range(w.gamma):
+            layer = g * w.gamma + l
+            assert torch.equal(st.k_out[layer][b, h, : len(rows)], st.k[layer][b, h].index_select(0, rows))
+            assert torch.equal(st.v_out[layer][b, h, : len(rows)], st.v[layer][b, h].index_select(0, rows))
+
+
 def test_lse_handoff_rejects_partial_arrays(device):
     w = _mini(seq_len=[300], n_groups=2, gamma=1)
     st = P.DeviceState(w, device)
