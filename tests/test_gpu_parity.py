@@ -173,6 +173,32 @@ def test_edge_cases(kw, device):
     run_and_check(_mini(**kw), device)
 
 
+def _random_workload(i):
+    """A seeded draw from the supported shape space (small enough for the oracle)."""
+    rng = np.random.default_rng(4242 + i)
+    d = int(rng.choice([64, 128]))
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    hkv = int(rng.choice([1, 2, 3, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8]))
+    w_obs = int(rng.integers(1, min(64, W.WKV_MAX_OBS_ROWS // G) + 1))
+    B = int(rng.choice([1, 1, 2, 3]))
+    seq_len, win, top_p, k = [], [], [], []
+    for _ in range(B):
+        L = w_obs + int(rng.choice([0, 1, int(rng.integers(2, 300)), int(rng.integers(300, 3000))]))
+        wn = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, int(rng.integers(1, 129))]))
+        nw = -(-(L - w_obs) // wn)
+        seq_len.append(L); win.append(wn); top_p.append(int(rng.integers(1, wn + 1)))
+        k.append(int(rng.choice([0, nw] + [int(rng.integers(0, nw + 1)) for _ in range(4)])))
+    n_groups = int(rng.choice([1, 2, 3])); gamma = int(rng.choice([1, 2, 3]))
+    return S.Workload(name=f"rand{i}", seed=9000 + i, dtype=dtype, n_groups=n_groups, gamma=gamma, n_q_heads=G * hkv,
+                      n_kv_heads=hkv, head_dim=d, w_obs=w_obs, seq_len=seq_len, win=win, top_p=top_p, k_windows=k)
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_shapes(i, device):
+    run_and_check(_random_workload(i), device)
+
+
 def test_large_logits_are_stable(device):
     # keys scaled so that logits reach hundreds: exponentials must never overflow
     w = _mini(seq_len=[2000], k_windows=[12], n_groups=1, gamma=1)
