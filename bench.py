@@ -219,6 +219,9 @@ def main():
     ap.add_argument("--no-lse-handoff", action="store_true",
                     help="skip the second measurement (softmax normalisers handed over by the caller)")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
+    ap.add_argument("--keep-padding", action="store_true",
+                    help="set WKV_KEEP_PADDING: compact-cache rows past n_keep are not zero-filled (matters for "
+                         "batches of mixed lengths; the default run zero-fills)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for hardware counters)")
     args = ap.parse_args()
@@ -236,7 +239,7 @@ def main():
     W.lib()
     device = torch.device("cuda:0")
     w = S.make_workload(args.workload)
-    st = P.DeviceState(w, device)
+    st = P.DeviceState(w, device, flags=W.WKV_KEEP_PADDING if args.keep_padding else 0)
     call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, None, st.k, st.v, st.k_out, st.v_out,
                           st.win_idx, st.tok_idx, st.n_keep, st.workspace)
     stream = torch.cuda.current_stream().cuda_stream
@@ -300,7 +303,7 @@ def main():
                                f"{w.n_q_heads}q/{w.n_kv_heads}kv heads, d={w.head_dim}, L={w.seq_len}, "
                                f"w_obs={w.w_obs}, win={sorted(set(w.win))}, top_p={sorted(set(w.top_p))}, "
                                f"k={w.k_windows}",
-                   "ms_per_group": ms_per_step / w.n_groups},
+                   "ms_per_group": ms_per_step / w.n_groups, "zero_fill_padding": not args.keep_padding},
         "roofline": roofline,
         "pipeline": {"bound": "hbm", "algorithmic_bytes": ab["pipeline"], "achieved": round(pipe_ach, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pipe_ach / HBM_PEAK_GBS, 4),

@@ -46,6 +46,12 @@ extern "C" {
 #define WKV_MAX_OBS_ROWS   256    /* largest G * w_obs                                    */
 #define WKV_MAX_WINDOWS    32768  /* largest NW of any sequence                           */
 
+/* wkv_problem.flags.  By default the gather zero-fills rows n_keep[b,h] .. nkeep_max-1 of every
+ * compact cache, so that the whole output is defined.  In a batch of mixed lengths these rows
+ * are a large share of the bytes written; a caller that never reads them (the decode step
+ * does not) sets WKV_KEEP_PADDING and they are left as they were. */
+#define WKV_KEEP_PADDING   1
+
 typedef enum {
   WKV_OK = 0,
   WKV_ERR_INVALID_ARG = -1,   /* null pointer, inconsistent sizes, out-of-range parameter */
@@ -85,6 +91,7 @@ typedef struct {
   int64_t q_stride_b, q_stride_h, q_stride_t;        /* q_obs                             */
   int64_t kv_stride_b, kv_stride_h, kv_stride_t;     /* full K and V (same for both)      */
   int64_t out_stride_b, out_stride_h, out_stride_t;  /* compact K_out and V_out           */
+  int32_t flags;             /* 0, or WKV_KEEP_PADDING                                    */
 } wkv_problem;
 
 /* Sizes derived from a problem; every output buffer below is sized by these. */
@@ -158,7 +165,8 @@ wkv_status wkv_topk_windows(const wkv_problem *problem, const float *s, int32_t 
  *   k_out_layers,
  *   v_out_layers           host arrays [n_layers] of device pointers to compact K_out / V_out
  * Row r < n_keep[b,h] of an output is a bit-exact copy of input row tok_idx[b,h,r]; rows
- * n_keep[b,h] .. nkeep_max-1 are zero-filled.  Inputs and outputs must not overlap.
+ * n_keep[b,h] .. nkeep_max-1 are zero-filled (left as they were with WKV_KEEP_PADDING).
+ * Inputs and outputs must not overlap.
  */
 wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
                             const void *const *k_layers, const void *const *v_layers,

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libwkv.so")
 
 WKV_OK, WKV_ERR_INVALID_ARG, WKV_ERR_UNSUPPORTED, WKV_ERR_WORKSPACE, WKV_ERR_HIP = 0, -1, -2, -3, -4
 WKV_F32, WKV_BF16 = 0, 1
+WKV_KEEP_PADDING = 1          # Problem(flags=...): leave compact-cache rows past n_keep untouched
 WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
 WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768
 WKV_N_STAGES = 5
@@ -42,6 +43,7 @@ class _Problem(C.Structure):
         ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_t", C.c_int64),
         ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_t", C.c_int64),
         ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64), ("out_stride_t", C.c_int64),
+        ("flags", C.c_int32),
     ]
 
 
@@ -114,7 +116,7 @@ class Problem:
                  seq_len: Sequence[int], win: Sequence[int], top_p: Sequence[int],
                  k_windows: Sequence[int], dtype: int, max_seq_len: Optional[int] = None,
                  scale: float = 0.0, q_strides=None, kv_strides=None, out_strides=None,
-                 nkeep_max: Optional[int] = None):
+                 nkeep_max: Optional[int] = None, flags: int = 0):
         B = len(seq_len)
         self._keep = [_i32(seq_len), _i32(win), _i32(top_p), _i32(k_windows)]
         if max_seq_len is None:
@@ -127,7 +129,7 @@ class Problem:
         out_strides = out_strides or (n_kv_heads * nkeep_max * d, nkeep_max * d, d)
         self.c = _Problem(B, n_q_heads, n_kv_heads, head_dim, w_obs, max_seq_len, dtype, scale,
                           self._keep[0], self._keep[1], self._keep[2], self._keep[3],
-                          *q_strides, *kv_strides, *out_strides)
+                          *q_strides, *kv_strides, *out_strides, flags)
 
     def ref(self):
         return C.byref(self.c)

@@ -33,10 +33,12 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(
   const int64_t irow = (int64_t)group * s.B * s.Hkv + bh;
   const int32_t *idx = tok_idx + irow * s.nkeep_max;
   const int nk = min(n_keep[irow], s.nkeep_max);
+  const int n_write = s.fill_padding ? s.nkeep_max : nk;   // rows past n_keep: zero-filled or left alone
   const int max_tok = s.t_stride + s.w_obs;      // token capacity of the full cache
   const int lane_in_row = threadIdx.x % LPR;
   const int row_in_pass = threadIdx.x / LPR;
   const int row0 = blockIdx.x * (ROWS_PER_PASS * GATHER_UNROLL) + row_in_pass;
+  if (blockIdx.x * (ROWS_PER_PASS * GATHER_UNROLL) >= n_write) return;
 
   u32x4 v[GATHER_UNROLL];
   int r[GATHER_UNROLL];
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(
   }
 #pragma unroll
   for (int u = 0; u < GATHER_UNROLL; ++u) {
-    if (r[u] < s.nkeep_max)
+    if (r[u] < n_write)
       __builtin_nontemporal_store(v[u], (u32x4 *)(dst + (int64_t)r[u] * row_bytes_out) + lane_in_row);
   }
 }

@@ -47,6 +47,7 @@ wkv_status validate(const wkv_problem *p, wkv_dims *dims) {
   if (p->head_dim != 64 && p->head_dim != 128) {
     set_error("head_dim %d is not supported (64 or 128)", p->head_dim); return WKV_ERR_UNSUPPORTED;
   }
+  if (p->flags & ~WKV_KEEP_PADDING) { set_error("unknown bits in flags (0x%x)", p->flags); return WKV_ERR_INVALID_ARG; }
   if (p->w_obs < 1) { set_error("w_obs must be >= 1"); return WKV_ERR_INVALID_ARG; }
   const int64_t G = p->n_q_heads / p->n_kv_heads;
   if (G * p->w_obs > WKV_MAX_OBS_ROWS) {
@@ -105,6 +106,7 @@ void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParam
   s->w_obs = p->w_obs; s->G = p->n_q_heads / p->n_kv_heads; s->M = dims.obs_rows;
   s->t_stride = dims.t_stride; s->nw_max = dims.nw_max; s->k_max = dims.k_max;
   s->nkeep_max = dims.nkeep_max; s->dtype = p->dtype;
+  s->fill_padding = (p->flags & WKV_KEEP_PADDING) ? 0 : 1;
   const double scale = p->scale > 0.0f ? (double)p->scale : 1.0 / std::sqrt((double)p->head_dim);
   s->c1 = (float)(scale * 1.4426950408889634074);
   s->q_sb = p->q_stride_b; s->q_sh = p->q_stride_h; s->q_st = p->q_stride_t;

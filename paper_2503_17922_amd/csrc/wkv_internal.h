@@ -49,6 +49,7 @@ struct Shape {
   int32_t M;          // G * w_obs softmax rows per KV head
   int32_t t_stride, nw_max, k_max, nkeep_max;
   int32_t dtype;
+  int32_t fill_padding;   // gather: zero the compact-cache rows past n_keep
   float c1;           // logit scale * log2(e): logits are handled in base-2 units
   int64_t q_sb, q_sh, q_st;
   int64_t kv_sb, kv_sh, kv_st;

@@ -30,10 +30,10 @@ def make_problem(w: S.Workload, **kw) -> W.Problem:
 class DeviceState:
     """All device tensors of one workload plus the outputs of one wkv_compress_groups call."""
 
-    def __init__(self, w: S.Workload, device, layers=True):
+    def __init__(self, w: S.Workload, device, layers=True, flags=0):
         self.w = w
         self.device = device
-        self.problem = make_problem(w)
+        self.problem = make_problem(w, flags=flags)
         self.dims = W.wkv_get_dims(self.problem)
         self.q = [w.q_obs_torch(g, device) for g in range(w.n_groups)]
         self.k = [w.kv_torch(S.KIND_K, l, device) for l in range(w.n_layers)]

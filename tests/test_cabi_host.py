@@ -70,12 +70,17 @@ def test_dims_of_the_named_configurations():
     (dict(kv_strides=(8 * 4096 * 128, 4096 * 128, 100)), W.WKV_ERR_INVALID_ARG),
     (dict(kv_strides=(8 * 4096 * 132, 4096 * 132, 132)), W.WKV_ERR_INVALID_ARG),   # not 16-byte rows
     (dict(seq_len=[300000], win=[8], k_windows=[1]), W.WKV_ERR_UNSUPPORTED),       # too many windows
+    (dict(flags=2), W.WKV_ERR_INVALID_ARG),                                        # unknown flag bit
 ])
 def test_invalid_problems_are_rejected_on_the_host(kw, status):
     with pytest.raises(W.WkvError) as e:
         W.wkv_get_dims(_problem(**kw))
     assert e.value.status == status
     assert len(str(e.value)) > 20
+
+
+def test_known_flags_are_accepted():
+    assert W.wkv_get_dims(_problem(flags=W.WKV_KEEP_PADDING)).nkeep_max == W.wkv_get_dims(_problem()).nkeep_max
 
 
 def test_stage_calls_validate_before_any_launch():

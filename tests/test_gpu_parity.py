@@ -355,6 +355,36 @@ def test_pyramid_budgets_per_group(device):
             assert not st.k_out[layer][b, h, n:].any() and not st.v_out[layer][b, h, n:].any(), what + " zero fill"
 
 
+def test_keep_padding_flag(device):
+    # WKV_KEEP_PADDING: identical indices and kept rows; rows past n_keep keep the caller's bytes
+    w = _mini(seq_len=[1000, 16, 333, 2048], win=[8, 8, 32, 128], top_p=[4, 8, 1, 64], k_windows=[20, 0, 3, 5])
+    ref = P.DeviceState(w, device); ref.compress()
+    st = P.DeviceState(w, device, flags=W.WKV_KEEP_PADDING); st.compress()
+    assert torch.equal(ref.tok_idx, st.tok_idx) and torch.equal(ref.n_keep, st.n_keep)
+    n_keep = st.n_keep.cpu().numpy()
+    padded = 0
+    for l in range(w.n_layers):
+        g = l // w.gamma
+        for b, h in itertools.product(range(w.batch), range(w.n_kv_heads)):
+            n = int(n_keep[g, b, h])
+            for out, want in ((st.k_out[l], ref.k_out[l]), (st.v_out[l], ref.v_out[l])):
+                assert torch.equal(out[b, h, :n], want[b, h, :n])
+                assert bool((out[b, h, n:] == 7.0).all()), "padding rows were written"
+                assert not want[b, h, n:].any()
+            padded += st.dims.nkeep_max - n
+    assert padded > 0
+    # the stage call honours the flag too
+    k_out = [torch.full_like(t, 3.0) for t in st.k_out[: w.gamma]]
+    v_out = [torch.full_like(t, 3.0) for t in st.v_out[: w.gamma]]
+    W.wkv_gather_group(st.problem, st.k[: w.gamma], st.v[: w.gamma], st.tok_idx[0], st.n_keep[0], k_out, v_out)
+    torch.cuda.synchronize()
+    for l in range(w.gamma):
+        for b, h in itertools.product(range(w.batch), range(w.n_kv_heads)):
+            n = int(n_keep[0, b, h])
+            assert torch.equal(k_out[l][b, h, :n], ref.k_out[l][b, h, :n]) and bool((k_out[l][b, h, n:] == 3.0).all())
+            assert torch.equal(v_out[l][b, h, :n], ref.v_out[l][b, h, :n]) and bool((v_out[l][b, h, n:] == 3.0).all())
+
+
 def test_other_layers_do_not_influence_indices(device):
     w = _mini(seq_len=[900], n_groups=1, gamma=3)
     st = P.DeviceState(w, device)
