@@ -172,10 +172,11 @@ def decode_leg(W, w, device, stream, steps):
     import torch
     torch.manual_seed(1007)                      # seeded N(0,1) caches: the timing does not depend on the values
     out = {}
-    n_rows = w.k_windows[0] * w.win[0] + w.w_obs
+    kept_rows = w.k_windows[0] * w.win[0] + w.w_obs
     esize = 2 if w.dtype == "bf16" else 4
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    for batch in (1, 64):
+    for batch, n_rows, label in ((1, kept_rows, "batch1"), (64, kept_rows, "batch64"),
+                                 (8, w.seq_len[0], "full_cache_batch8")):
         cap = n_rows + 64
         shape = W.DecodeShape(batch=batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                               capacity=cap, dtype=W.WKV_BF16 if w.dtype == "bf16" else W.WKV_F32)
@@ -189,7 +190,7 @@ def decode_leg(W, w, device, stream, steps):
         ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
         n_valid = torch.full((batch, H), n_rows, dtype=torch.int32, device=device)
 
-        def run(n):
+        def run(n, n_rows=n_rows, n_valid=n_valid):
             for _ in range(n):
                 n_valid.fill_(n_rows)            # stay at the same length: the fill is part of the loop for both counts
                 W.wkv_decode_step(shape, q, kn, vn, kc, vc, n_valid, res, ws, stream)
@@ -200,12 +201,16 @@ def decode_leg(W, w, device, stream, steps):
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / steps * 1e3
         nbytes = 2 * batch * H * (n_rows + 1) * d * esize
-        out[f"batch{batch}"] = {"ms_per_layer_step": round(ms, 4), "algorithmic_bytes": nbytes,
+        out[label] = {"ms_per_layer_step": round(ms, 4), "algorithmic_bytes": nbytes,
                                 "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                 "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                 "rows_per_kv_head": n_rows + 1}
-    out["note"] = ("wkv_decode_step on synthetic caches of the retained size; times include one tiny fill kernel "
-                   "per step and the launch overhead of 3 kernels (latency-bound at batch 1)")
+    # the method's decode-time gain: attention time per sequence over the whole prefix / over what was kept
+    out["attention_speedup_vs_full_cache"] = round((out["full_cache_batch8"]["ms_per_layer_step"] / 8) /
+                                                   (out["batch64"]["ms_per_layer_step"] / 64), 2)
+    out["note"] = ("wkv_decode_step on synthetic caches of the retained size (batch1, batch64) and of the whole prefix "
+                   "(full_cache_batch8, the same bytes as batch64); times include one tiny fill kernel per step and "
+                   "the launch overhead of 3 kernels (latency-bound at batch 1)")
     return out
 
 
