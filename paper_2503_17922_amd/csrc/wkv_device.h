@@ -48,25 +48,25 @@ __device__ __forceinline__ float fold_partials(const float2 *__restrict__ part, 
 }
 
 // ---- MFMA building blocks (bf16, v_mfma_f32_16x16x32_bf16) ----------------------------------
-constexpr int MF_THREADS = 256;
-constexpr int MF_WAVES = 4;
+constexpr int MF_THREADS = 256;           // per row half (see score_mfma_kernel)
+constexpr int MF_WAVES = 4;              // waves that share the key tiles of an iteration
 constexpr int MF_KT = 2;                 // key tiles of 16 per wave iteration (share each B fragment)
 constexpr float MF_BIG = 1.0e30f;        // a tile sum above this re-references the row (2^100)
 
 // Arrange the M query rows of KV head h as MFMA B fragments in LDS.
 // Fragment (mt, ks) is 64 x 16 bytes: lane l holds row 16*mt + l%16, channels 32*ks + 8*(l/16)..+7.
-template <int D, int MT>
+template <int D, int MT, int NT>                          // NT threads stage MT row tiles
 struct QStage {
   static constexpr int KS = D / 32;
   static constexpr int TOTAL = MT * KS * 64;               // 16-byte pieces of the fragments
-  static constexpr int N = (TOTAL + MF_THREADS - 1) / MF_THREADS;   // per thread
+  static constexpr int N = (TOTAL + NT - 1) / NT;          // per thread
   uint4 v[N];
   // Issue every load of this thread at once (independent of each other, so their latencies
   // overlap; a load-then-store loop would pay one round trip per piece).
   __device__ __forceinline__ void load(const Shape &s, const void *qbase, int b, int h) {
 #pragma unroll
     for (int k = 0; k < N; ++k) {
-      const int i = threadIdx.x + k * MF_THREADS;
+      const int i = threadIdx.x + k * NT;
       const int l = i & 63, f = i >> 6, ks = f % KS, mt = f / KS;
       const int r = mt * 16 + (l & 15);
       v[k] = make_uint4(0u, 0u, 0u, 0u);
@@ -80,7 +80,7 @@ struct QStage {
   __device__ __forceinline__ void store(uint4 *qfrag) const {
 #pragma unroll
     for (int k = 0; k < N; ++k)
-      if (threadIdx.x + k * MF_THREADS < TOTAL) qfrag[threadIdx.x + k * MF_THREADS] = v[k];
+      if (threadIdx.x + k * NT < TOTAL) qfrag[threadIdx.x + k * NT] = v[k];
   }
 };
 

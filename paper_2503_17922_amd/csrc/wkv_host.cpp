@@ -129,13 +129,14 @@ static int64_t count_items(const BatchParams &bp, int32_t B, int64_t rows_per_se
 }
 
 // Keys per workgroup.  The score kernels keep three workgroups resident on each of the 256
-// compute units, and a workgroup's fixed cost (staging the query fragments, the first key
-// load, the epilogue) is several microseconds: the launch is fastest when its non-empty work
-// items fill those 768 slots a whole number of times with chunks as long as the kernels allow.
+// compute units (one, with more than 128 softmax rows), and a workgroup's fixed cost (staging
+// the query fragments, the first key load, the epilogue) is several microseconds: the launch is
+// fastest when its non-empty work items fill those `slots` a whole number of times with chunks
+// as long as the kernels allow.
 // Chunks are multiples of 128 keys (one iteration of a workgroup); `drop` keys at the end of
 // every sequence are not part of the pass.
-static int32_t pick_chunk(const BatchParams &bp, int32_t B, int64_t rows_per_seq, int32_t drop, int32_t lo, int32_t hi) {
-  const int64_t slots = 768;
+static int32_t pick_chunk(const BatchParams &bp, int32_t B, int64_t rows_per_seq, int32_t drop, int32_t lo, int32_t hi,
+                          int64_t slots) {
   int64_t total = 0;
   for (int32_t b = 0; b < B; ++b) total += (int64_t)std::max(bp.seq[b].L - drop, 0) * rows_per_seq;
   if (total <= 0) return lo;
@@ -151,12 +152,13 @@ static int32_t pick_chunk(const BatchParams &bp, int32_t B, int64_t rows_per_seq
 ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   ScorePlan pl;
   pl.m_pad = (s.M + 15) / 16 * 16;
-  pl.mfma = (s.dtype == WKV_BF16) && pl.m_pad <= 128;
+  pl.mfma = (s.dtype == WKV_BF16) && pl.m_pad <= 256;
   const int64_t rows_per_seq = (int64_t)s.Hkv * n_groups;
   const int32_t Lmax = s.t_stride + s.w_obs;
-  pl.chunk1 = pick_chunk(bp, s.B, rows_per_seq, 0, 256, MAX_CHUNK1);
+  const int64_t slots = pl.m_pad <= 128 ? 768 : 256;
+  pl.chunk1 = pick_chunk(bp, s.B, rows_per_seq, 0, 256, MAX_CHUNK1, slots);
   pl.n_chunks1 = (int32_t)ceil_div(Lmax, pl.chunk1);
-  pl.chunk2 = pick_chunk(bp, s.B, rows_per_seq, s.w_obs, 256, MAX_CHUNK2);
+  pl.chunk2 = pick_chunk(bp, s.B, rows_per_seq, s.w_obs, 256, MAX_CHUNK2, slots);
   pl.n_chunks2 = (int32_t)ceil_div(s.t_stride > 0 ? s.t_stride : 1, pl.chunk2);
   // every pass-2 workgroup re-reads rows * n_chunks1 partials when it folds them itself: worth
   // it (one launch less) only while that stays a few KB

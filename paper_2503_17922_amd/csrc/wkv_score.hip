@@ -17,11 +17,11 @@
 // over; pass 1 and the fold are then skipped and the keys are read once.
 //
 // Two kernel families implement the passes:
-//   * MFMA (bf16 inputs, M <= 128): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
+//   * MFMA (bf16 inputs, any M <= 256): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
 //     loaded straight from global memory into registers in operand layout, so K never passes
 //     through LDS and the four waves of a workgroup never synchronise in the loop; the
 //     query rows are the B operand, read as pre-arranged fragments from LDS.
-//   * generic (fp32 inputs, or M > 128): plain fp32 FMAs, thread-per-row for the stats,
+//   * generic (fp32 inputs): plain fp32 FMAs, thread-per-row for the stats,
 //     thread-per-key for the scores, the other operand broadcast from LDS.
 #include "wkv_device.h"
 #include "wkv_pool.h"
@@ -195,21 +195,31 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
 // row statistics of pass 1 are in-lane accumulations merged once per chunk, and the column
 // sums of pass 2 are in-lane adds over the row tiles plus one 16-lane DPP reduction.
 // PASS 1: stats.  PASS 2: scores.
-template <int D, int MT, int PASS>
-__global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
+//
+// Up to 128 rows (HV = 1) a workgroup is 4 waves that take different key tiles of an iteration
+// and all MT row tiles each; three workgroups share a CU.  With 129..256 rows (HV = 2: eight
+// query heads per KV head at 32 observation queries) a workgroup is 8 waves: waves 0-3 work on
+// row tiles 0..MT-1 and waves 4-7 on row tiles MT..2MT-1 of the same key tiles (the second
+// read of a key tile hits the CU's vector cache), the 64 KB of query fragments allow one
+// workgroup per CU, and pass 2 adds the column sums of the two halves in its epilogue.
+template <int D, int MT, int HV, int PASS>
+__global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    const float *__restrict__ lse_g,
                                                                    float *__restrict__ t_out,
                                                                    float *__restrict__ s_pool) {
   constexpr int KS = D / 32;
   constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
-  __shared__ uint4 qfrag[MT * KS * 64];
-  __shared__ float2 wave_part[PASS == 1 ? MF_WAVES : 1][MT * 16];
+  constexpr int NT = MF_THREADS * HV;                 // threads of the workgroup
+  constexpr int MTT = MT * HV;                        // row tiles of the workgroup
+  constexpr int TS_LEN = MAX_CHUNK2 + 256;            // token scores of a chunk + the scrap area
+  __shared__ uint4 qfrag[MTT * KS * 64];
+  __shared__ float2 wave_part[PASS == 1 ? MF_WAVES * HV : 1][MT * 16];
   // Pass 2 collects the chunk's token scores here and writes them out once at the end: global
   // stores inside the loop would share the vector-memory counter with the key prefetch and make
   // every wait for keys also wait for store acknowledgements.
-  __shared__ __attribute__((aligned(16))) float t_s[PASS == 2 ? MAX_CHUNK2 + 256 : 1];
-  __shared__ float lse_s[PASS == 2 ? MT * 16 : 1];
+  __shared__ __attribute__((aligned(16))) float t_s[PASS == 2 ? HV * TS_LEN : 1];
+  __shared__ float lse_s[PASS == 2 ? MTT * 16 : 1];
 
   // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
   // are the ones most likely still held by the memory-side cache.
@@ -221,6 +231,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   const int n_review = L - s.w_obs;
   const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = wave / MF_WAVES, kw = wave % MF_WAVES;   // row half, key tile slot of this wave
   const int col = lane & 15, quad = lane >> 4;
 
   const int chunk = PASS == 1 ? pl.chunk1 : pl.chunk2;
@@ -232,22 +243,22 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
     const int cend_fill = min(c0 + chunk, s.t_stride);
     if (c0 >= n_review) {
       if (!s_pool)
-        for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = 0.0f;
+        for (int j = c0 + threadIdx.x; j < cend_fill; j += NT) trow[j] = 0.0f;
       return;
     }
   }
   if (PASS == 1 && c0 >= L) {                         // a chunk past the end of a short sequence
-    for (int r = threadIdx.x; r < pl.m_pad; r += MF_THREADS)
+    for (int r = threadIdx.x; r < pl.m_pad; r += NT)
       partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(-INFINITY, 0.0f);
     return;
   }
   // Loads that depend on nothing staged below go out first, so that their latencies overlap: the
   // query fragments of this workgroup and the first key tile of every wave.
-  QStage<D, MT> qstage;
+  QStage<D, MTT, NT> qstage;
   qstage.load(s, gp.q[g], b, h);
   const int cend = min(c0 + chunk, limit);
   const uint16_t *kbase = (const uint16_t *)gp.k[g] + (int64_t)b * s.kv_sb + (int64_t)h * s.kv_sh + quad * 8;
-  int j0 = c0 + wave * STEP;
+  int j0 = c0 + kw * STEP;
   KFrags<KS> ka, kb;
   load_k<KS>(ka, kbase, s.kv_st, j0, col, max(cend, 1));
 
@@ -255,7 +266,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
     // The base-2 log-sum-exp of the MT*16 rows, into LDS.  With few chunks per row the workgroup
     // folds the (m, z) partials of pass 1 itself (TPR adjacent lanes share a row; the query
     // and key loads issued above are in flight meanwhile); otherwise a fold launch or the caller provided them.
-    constexpr int TPR = MF_THREADS / (MT * 16);
+    constexpr int TPR = NT / (MTT * 16);
     const int r = threadIdx.x / TPR, part = threadIdx.x % TPR;
     if (pl.fold_in_pass2) {
       float m = -INFINITY, z = 0.0f;
@@ -273,11 +284,11 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
   qstage.store(qfrag);
   __syncthreads();
 
-  // per-lane row constants: this lane's query row of row tile mt is 16*mt + col
+  // per-lane row constants: this lane's query row of its row tile mt is 16*(half*MT + mt) + col
   float lse_r[MT], mref[MT], zsum[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    lse_r[mt] = PASS == 2 ? lse_s[mt * 16 + col] : 0.0f;
+    lse_r[mt] = PASS == 2 ? lse_s[(half * MT + mt) * 16 + col] : 0.0f;
     mref[mt] = -INFINITY;
     zsum[mt] = 0.0f;
   }
@@ -310,7 +321,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       if (mt < MT) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const uint4 qraw = qfrag[(mt * KS + ks) * 64 + lane];
+          const uint4 qraw = qfrag[((half * MT + mt) * KS + ks) * 64 + lane];
           const bf16x8 qb = *(const bf16x8 *)&qraw;
 #pragma unroll
           for (int n = 0; n < MF_KT; ++n)
@@ -342,7 +353,7 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
         // query io iff j <= n_review + io) and the end of the sequence; redo their sums
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const int r = mt * 16 + col;
+          const int r = (half * MT + mt) * 16 + col;
           const int last_vis = r < s.M ? n_review + (r % s.w_obs) : -1;
           float a = 0.0f;
 #pragma unroll
@@ -390,7 +401,8 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       // t_j: the lane's partial column sums, summed over the 16 lanes (rows 16*mt + 0..15)
       // Every lane stores (lanes other than the first of each 16 into a scrap area past the
       // chunk): a store under a lane predicate would put a branch into the middle of the block.
-      float *dst = col == 0 ? t_s + (j0 - c0) + quad * 4 : t_s + MAX_CHUNK2 + lane * 4;
+      float *ts = t_s + half * TS_LEN;
+      float *dst = col == 0 ? ts + (j0 - c0) + quad * 4 : ts + MAX_CHUNK2 + lane * 4;
 #pragma unroll
       for (int n = 0; n < MF_KT; ++n) {
 #pragma unroll
@@ -410,17 +422,21 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
 
   if (PASS == 2) {
     __syncthreads();
+    if (HV == 2) {                                    // column sums of the second half of the rows
+      for (int j = threadIdx.x; j < cend - c0; j += NT) t_s[j] += t_s[TS_LEN + j];
+      __syncthreads();
+    }
     if (s_pool) {
       // Eq. 3-4 on the chunk's token scores while they are in LDS: the chunk starts on a window
       // boundary and no window but the sequence's last (partial) one ends outside it
       const SeqParam sp = bp.seq[b];
       const int w0 = c0 / sp.win, w1 = (cend + sp.win - 1) / sp.win;
       float *srow = s_pool + row * s.nw_max;
-      for (int w = w0 + threadIdx.x; w < w1; w += MF_THREADS)
+      for (int w = w0 + threadIdx.x; w < w1; w += NT)
         srow[w] = pool_window(t_s - c0, w, sp.win, n_review, sp.p);
     } else {
       const int cend_fill = min(c0 + chunk, s.t_stride);
-      for (int j = c0 + threadIdx.x; j < cend_fill; j += MF_THREADS) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
+      for (int j = c0 + threadIdx.x; j < cend_fill; j += NT) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
     }
   }
   if (PASS == 1) {
@@ -436,9 +452,10 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
       if (quad == 0) wave_part[wave][mt * 16 + col] = make_float2(m, z);
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < pl.m_pad; r += MF_THREADS) {   // m_pad <= MT*16
-      float m = wave_part[0][r].x, z = wave_part[0][r].y;
-      for (int w = 1; w < MF_WAVES; ++w) merge_stats(m, z, wave_part[w][r].x, wave_part[w][r].y);
+    for (int r = threadIdx.x; r < pl.m_pad; r += NT) {           // m_pad <= MTT*16
+      const int w0 = r / (MT * 16) * MF_WAVES, rr = r % (MT * 16);   // the waves that hold row r
+      float m = wave_part[w0][rr].x, z = wave_part[w0][rr].y;
+      for (int w = 1; w < MF_WAVES; ++w) merge_stats(m, z, wave_part[w0 + w][rr].x, wave_part[w0 + w][rr].y);
       partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(m, z);
     }
   }
@@ -447,18 +464,18 @@ __global__ __launch_bounds__(MF_THREADS, 3) void score_mfma_kernel(Shape s, Batc
 // =========================================================================================
 // launch
 // =========================================================================================
-template <int D, int MT>
+template <int D, int MT, int HV>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                               int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
                               float *s_pool, hipStream_t stream, hipEvent_t mid) {
-  dim3 block(MF_THREADS);
+  dim3 block(MF_THREADS * HV);
   hipError_t e;
   if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
   } else {
     dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-    hipLaunchKernelGGL((score_mfma_kernel<D, MT, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
@@ -470,7 +487,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
   ScorePlan pl2 = pl;
   if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
   return hipGetLastError();
 }
 
@@ -511,10 +528,14 @@ hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
 #define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
+  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM, 1>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
     WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
     WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
 #undef WKV_MFMA_CASE
+    if (mt <= 16) {                                    // 129..256 rows: two halves of 8 row tiles
+      if (s.d == 128) return launch_mfma<128, 8, 2>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
+      if (s.d == 64) return launch_mfma<64, 8, 2>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
+    }
     return hipErrorInvalidValue;
   }
   if (s.dtype == WKV_BF16) {

@@ -163,7 +163,10 @@ def _mini(**kw):
     dict(n_q_heads=12, n_kv_heads=2, w_obs=4, seq_len=[5000], k_windows=[30]),    # Qwen-like G=6, alpha=4
     dict(n_q_heads=4, n_kv_heads=4, w_obs=1),                             # a single observation query per head
     dict(head_dim=64, seq_len=[3000], k_windows=[40]),
-    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[1500]),           # 256 rows: generic kernels, bf16
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[1500]),           # 256 rows: two row halves per workgroup
+    dict(n_q_heads=10, n_kv_heads=2, w_obs=32, seq_len=[9000, 700], win=[16, 8], top_p=[8, 8], k_windows=[40, 9]),   # 160 rows, several chunks
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, head_dim=64, seq_len=[2500], win=[24], top_p=[5], k_windows=[17]),     # 256 rows, d=64, pooling in the selection kernel
+    dict(n_q_heads=14, n_kv_heads=2, w_obs=19, seq_len=[3100]),           # 133 rows: 9 row tiles
     dict(dtype="f32", head_dim=128, seq_len=[900]),
     dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=1, w_obs=64, seq_len=[600]),
     dict(n_groups=1, gamma=1, seq_len=[4097], win=[16], top_p=[8], k_windows=[31]),
@@ -287,6 +290,8 @@ def test_lse_handoff_small_configs(device):
     _check_lse_handoff(S.make_workload("c2"), device, groups_oracle=[0])          # bf16, MFMA kernels, outlier channels
     w = _mini(seq_len=[777, 130, 2049], win=[8, 16, 32], top_p=[8, 5, 16], k_windows=[20, 3, 11], n_groups=2, gamma=2)
     _check_lse_handoff(w, device, groups_oracle=[0, 1])                           # ragged batch, two groups
+    w = _mini(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[2100, 600], win=[8, 16], top_p=[8, 8], k_windows=[20, 5])
+    _check_lse_handoff(w, device, groups_oracle=[0, 1])                           # 256 softmax rows per KV head
 
 
 def test_lse_handoff_full_model(device):
