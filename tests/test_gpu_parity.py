@@ -122,6 +122,13 @@ def test_config_c4_full_model(device):
             assert want <= kept, f"planted span at {s0} not kept in g{g} h{h}"
 
 
+def test_config_c4_eight_query_heads_per_kv_head(device):
+    # the 32K configuration with 64 query heads on 8 KV heads (70B-class): 256 softmax rows per KV
+    # head, the two-half workgroups at their full chunk plan (3 groups of 2 layers keep it light)
+    w = S.scaled_workload(S.make_workload("c4"), name="c4g8", n_q_heads=64, n_groups=3, gamma=2)
+    run_and_check(w, device, n_oracle=6, n_gather_cpu=8, check_stage_group=1)
+
+
 def test_config_c5_batched_mixed(device):
     w = S.make_workload("c5")
     run_and_check(w, device, n_oracle=32, n_gather_cpu=16, check_stage_group=5)
