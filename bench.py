@@ -231,7 +231,7 @@ def main():
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (sequences, KV heads and layer groups are independent: shard them across processes)",
               file=sys.stderr)
         sys.exit(2)
 
