@@ -88,6 +88,9 @@ def test_decode_full_size_cache(device):
     dict(dtype="f32", head_dim=128, n_q_heads=3, n_kv_heads=3, w_obs=4),                # G = 1
     dict(dtype="bf16", head_dim=64, n_q_heads=12, n_kv_heads=2, w_obs=4),               # G = 6, d = 64
     dict(dtype="bf16", head_dim=128, n_q_heads=16, n_kv_heads=2, w_obs=8),              # G = 8
+    dict(dtype="bf16", head_dim=128, n_q_heads=14, n_kv_heads=2, w_obs=8),              # G = 7 (28q/4kv models)
+    dict(dtype="bf16", head_dim=64, n_q_heads=10, n_kv_heads=2, w_obs=8),               # G = 5
+    dict(dtype="f32", head_dim=128, n_q_heads=6, n_kv_heads=2, w_obs=8),                # G = 3, fp32
     dict(dtype="bf16", head_dim=128, n_q_heads=8, n_kv_heads=2, w_obs=16, seq_len=[16], k_windows=[0]),   # only the observation rows
 ])
 def test_decode_shapes(device, kw):
