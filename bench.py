@@ -80,7 +80,7 @@ def cpu_baseline(w, st, budget_s=10.0):
     import numpy as np
     import torch
     from oracle import wkv_oracle as O
-    from tests import parity as P
+    from paper_2503_17922_amd import synthetic as P
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -238,7 +238,7 @@ def main():
     import torch
     import paper_2503_17922_amd as W
     import wkv_synth as S
-    from tests import parity as P
+    from paper_2503_17922_amd import synthetic as P
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     W.lib()
