@@ -48,6 +48,12 @@ def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check
     t_dev, s_dev, wi, ti, nk = st.stages(g0)
     assert np.array_equal(wi.cpu().numpy()[..., : st.dims.k_max], win_idx[g0]) and np.array_equal(ti.cpu().numpy(), tok_idx[g0])
     assert np.array_equal(nk.cpu().numpy(), n_keep[g0])
+    # the gather stage, one layer at a time (as prefill would produce them), equals the batched gather
+    for l in range(g0 * w.gamma, (g0 + 1) * w.gamma):
+        ko = torch.full_like(st.k_out[l], 9.0); vo = torch.full_like(st.v_out[l], 9.0)
+        W.wkv_gather_group(st.problem, [st.k[l]], [st.v[l]], ti, nk, [ko], [vo])
+        torch.cuda.synchronize()
+        assert torch.equal(ko, st.k_out[l]) and torch.equal(vo, st.v_out[l]), f"{w.name}: stage gather of layer {l}"
     t_host = t_dev.cpu().numpy().astype(np.float64)[..., : st.dims.t_stride]
     s_host = s_dev.cpu().numpy().astype(np.float64)[..., : st.dims.nw_max]
 
