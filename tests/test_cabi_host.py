@@ -161,3 +161,21 @@ def test_group_budgets_match_eq_5_to_7(H, lam, total):
         W.wkv_group_budgets(total, 0, lam)
     with pytest.raises(W.WkvError):
         W.wkv_group_budgets(total, H, 0.0)
+
+
+def test_header_is_c99_and_library_links_from_c(tmp_path):
+    # include/wkv.h compiled by gcc as pedantic C99; the program calls the host-only entry points
+    import shutil, subprocess, os
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    W.lib()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(W.LIB_PATH)
+    exe = str(tmp_path / "cabi_host")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c", "cabi_host.c"), "-L", libdir, "-lwkv", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib", "-o", exe], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()
+    d = W.wkv_get_dims(_problem())
+    assert out[:5] == ["0", str(d.obs_rows), str(d.nw_max), str(d.k_max), str(d.nkeep_max)]
+    assert int(out[5]) == W.wkv_workspace_bytes(_problem(), 1) and out[6] == "ok"
