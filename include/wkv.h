@@ -60,7 +60,7 @@ typedef enum {
   WKV_ERR_HIP         = -4    /* a HIP call or kernel launch failed                        */
 } wkv_status;
 
-typedef enum { WKV_F32 = 0, WKV_BF16 = 1 } wkv_dtype;
+typedef enum { WKV_F32 = 0, WKV_BF16 = 1, WKV_F16 = 2 } wkv_dtype;   /* fp32, bfloat16, IEEE half */
 
 /*
  * One batch of sequences.  The same description serves one layer group or several (the

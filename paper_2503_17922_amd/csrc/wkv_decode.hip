@@ -6,7 +6,7 @@
 // the two caches; what matters is that the arithmetic per row stays well below the memory rate.
 //
 //   partial kernel  grid (splits, B*Hkv): a workgroup walks one key range of one KV head.
-//                   fp32 inputs: everything on the vector ALU, as follows.  bf16 inputs: the
+//                   fp32 inputs: everything on the vector ALU, as follows.  16-bit inputs: the
 //                   scores come from the matrix pipe (decode_partial_mfma_kernel below), the
 //                   value side keeps this layout.  A
 //                   16-byte piece of a row per lane, so D*esize/16 lanes cover a row and a wave
@@ -25,7 +25,17 @@ constexpr int DEC_THREADS = 256;
 constexpr int DEC_WAVES = DEC_THREADS / 64;
 constexpr int DEC_U = 4;            // row tiles per wave batch (loads in flight: 2 * DEC_U per lane)
 
+struct half_t { uint16_t bits; };             // element tag of IEEE half tensors (uint16_t stands for bfloat16)
+
 template <typename T> struct Piece;           // the 16-byte piece of a row held by one lane
+template <> struct Piece<half_t> {
+  static constexpr int E = 8;
+  static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8]) {
+    const f16x8 h = __builtin_bit_cast(f16x8, r);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+  }
+};
 template <> struct Piece<uint16_t> {
   static constexpr int E = 8;
   static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8]) {
@@ -234,15 +244,15 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeShape
   merge_waves_and_store<D, G>(s, wave_state, bh, split, part);
 }
 
-// ---- bf16: scores on the matrix pipe ---------------------------------------------------------
-// The G query rows (padded to 16) are the B operand of v_mfma_f32_16x16x32_bf16 and 16 cache rows
+// ---- bf16 / fp16: scores on the matrix pipe --------------------------------------------------
+// The G query rows (padded to 16) are the B operand of v_mfma_f32_16x16x32_bf16 (_f16) and 16 cache rows
 // the A operand, loaded in operand layout as in the score kernels, so a block of 16 rows costs
 // D/32 MFMAs instead of 16 * G dot-product reductions, and each lane takes the exponent of 4
 // scores instead of G per row.  The probabilities go through a small per-wave LDS tile to the
 // value side, which keeps the row-piece layout above (V is contracted over rows, the wrong way
 // round for an MFMA operand).  Every lane of a wave uses the same running maximum per head, so
 // the lane groups' outputs simply add up at the end.
-template <int D, int G>
+template <int D, int G, bool F16>
 __global__ __launch_bounds__(DEC_THREADS) void decode_partial_mfma_kernel(
     DecodeShape s, const uint16_t *__restrict__ q_new, const uint16_t *__restrict__ k_new,
     const uint16_t *__restrict__ v_new, uint16_t *k_cache, uint16_t *v_cache, const int32_t *__restrict__ n_valid,
@@ -321,7 +331,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_mfma_kernel(
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8 *)&kcur[ks], qb[ks], acc, 0, 0, 0);
+      acc = mfma_16x16x32<F16>(*(const bf16x8 *)&kcur[ks], qb[ks], acc);
     const int r0 = c0 + blk * 16;
     float sc[4];
 #pragma unroll
@@ -365,7 +375,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_mfma_kernel(
       float pg[GP], vf[E];
 #pragma unroll
       for (int i = 0; i < GP; i += 4) *(float4 *)&pg[i] = *(const float4 *)&p_s[wave][t * KPT + slot][i];
-      Piece<uint16_t>::unpack(vcur[t], vf);
+      if constexpr (F16) Piece<half_t>::unpack(vcur[t], vf); else Piece<uint16_t>::unpack(vcur[t], vf);
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -449,8 +459,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_combine_kernel(DecodeShape
 template <typename T, int D, int G>
 static void launch_partial_g(const DecodeShape &s, dim3 grid, const void *q, const void *kn, const void *vn, void *kc,
                              void *vc, const int32_t *n_valid, float *part, hipStream_t stream) {
-  if constexpr (sizeof(T) == 2)     // bf16: scores on the matrix pipe
-    hipLaunchKernelGGL((decode_partial_mfma_kernel<D, G>), grid, dim3(DEC_THREADS), 0, stream, s, (const uint16_t *)q,
+  if constexpr (sizeof(T) == 2)     // bf16 / fp16: scores on the matrix pipe
+    hipLaunchKernelGGL((decode_partial_mfma_kernel<D, G, sizeof(T) == 2 && !__is_same(T, uint16_t)>), grid, dim3(DEC_THREADS), 0, stream, s, (const uint16_t *)q,
                        (const uint16_t *)kn, (const uint16_t *)vn, (uint16_t *)kc, (uint16_t *)vc, n_valid, part);
   else
     hipLaunchKernelGGL((decode_partial_kernel<T, D, G>), grid, dim3(DEC_THREADS), 0, stream, s, (const T *)q,
@@ -478,6 +488,9 @@ hipError_t launch_decode(const DecodeShape &s, const void *q_new, const void *k_
   if (s.dtype == WKV_BF16)
     e = s.d == 128 ? launch_partial<uint16_t, 128>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream)
                    : launch_partial<uint16_t, 64>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream);
+  else if (s.dtype == WKV_F16)
+    e = s.d == 128 ? launch_partial<half_t, 128>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream)
+                   : launch_partial<half_t, 64>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream);
   else
     e = s.d == 128 ? launch_partial<float, 128>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream)
                    : launch_partial<float, 64>(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, part, stream);

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(
 hipError_t launch_gather(const Shape &s, const LayerPtrs &lp, int32_t n_layers, int32_t gamma,
                          const int32_t *tok_idx, const int32_t *n_keep, hipStream_t stream) {
   if (s.nkeep_max <= 0) return hipSuccess;
-  const int64_t esize = s.dtype == WKV_BF16 ? 2 : 4;
+  const int64_t esize = elem_bytes(s.dtype);
   const int lpr = (int)(s.d * esize / 16);   // 8 (bf16 d=64), 16, 16, or 32 (f32 d=128)
   const int rows_per_block = GATHER_THREADS / lpr * GATHER_UNROLL;
   dim3 grid((s.nkeep_max + rows_per_block - 1) / rows_per_block, s.B * s.Hkv, n_layers * 2);

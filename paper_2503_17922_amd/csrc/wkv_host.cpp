@@ -41,7 +41,7 @@ wkv_status validate(const wkv_problem *p, wkv_dims *dims) {
   if ((int64_t)p->batch * p->n_kv_heads > 65535) {
     set_error("batch * n_kv_heads exceeds 65535 (launch grid limit); split the call"); return WKV_ERR_UNSUPPORTED;
   }
-  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16) {
+  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16 && p->dtype != WKV_F16) {
     set_error("unknown dtype %d", p->dtype); return WKV_ERR_INVALID_ARG;
   }
   if (p->head_dim != 64 && p->head_dim != 128) {
@@ -63,7 +63,7 @@ wkv_status validate(const wkv_problem *p, wkv_dims *dims) {
     set_error("token strides must be >= head_dim"); return WKV_ERR_INVALID_ARG;
   }
   // 16-byte vector loads: every row start must be 16-byte aligned relative to the base.
-  const int64_t vec = p->dtype == WKV_BF16 ? 8 : 4;
+  const int64_t vec = 16 / elem_bytes(p->dtype);
   const int64_t strides[9] = {p->q_stride_b, p->q_stride_h, p->q_stride_t, p->kv_stride_b, p->kv_stride_h,
                               p->kv_stride_t, p->out_stride_b, p->out_stride_h, p->out_stride_t};
   for (int i = 0; i < 9; ++i) {
@@ -152,7 +152,7 @@ static int32_t pick_chunk(const BatchParams &bp, int32_t B, int64_t rows_per_seq
 ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   ScorePlan pl;
   pl.m_pad = (s.M + 15) / 16 * 16;
-  pl.mfma = (s.dtype == WKV_BF16) && pl.m_pad <= 256;
+  pl.mfma = s.dtype != WKV_F32;      // 16-bit inputs: matrix-pipe kernels (m_pad <= 256 always holds)
   const int64_t rows_per_seq = (int64_t)s.Hkv * n_groups;
   const int32_t Lmax = s.t_stride + s.w_obs;
   const int64_t slots = pl.m_pad <= 128 ? 768 : 256;
@@ -200,7 +200,7 @@ wkv_status validate_decode(const wkv_decode_shape *p, Decode *out) {
   }
   const int32_t G = p->n_q_heads / p->n_kv_heads;
   if (G > 8) { set_error("n_q_heads / n_kv_heads = %d is not supported by the decode step (at most 8)", G); return WKV_ERR_UNSUPPORTED; }
-  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16) { set_error("unknown dtype %d", p->dtype); return WKV_ERR_INVALID_ARG; }
+  if (p->dtype != WKV_F32 && p->dtype != WKV_BF16 && p->dtype != WKV_F16) { set_error("unknown dtype %d", p->dtype); return WKV_ERR_INVALID_ARG; }
   if (p->head_dim != 64 && p->head_dim != 128) {
     set_error("head_dim %d is not supported (64 or 128)", p->head_dim); return WKV_ERR_UNSUPPORTED;
   }
@@ -208,7 +208,7 @@ wkv_status validate_decode(const wkv_decode_shape *p, Decode *out) {
     set_error("scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))"); return WKV_ERR_INVALID_ARG;
   }
   if (p->capacity < 1) { set_error("capacity must be >= 1"); return WKV_ERR_INVALID_ARG; }
-  const int64_t vec = p->dtype == WKV_BF16 ? 8 : 4;
+  const int64_t vec = 16 / elem_bytes(p->dtype);
   const int64_t strides[3] = {p->cache_stride_b, p->cache_stride_h, p->cache_stride_t};
   for (int i = 0; i < 3; ++i)
     if (strides[i] < 0 || strides[i] % vec != 0) {

@@ -8,6 +8,8 @@
 
 namespace wkv {
 
+inline int64_t elem_bytes(int32_t dtype) { return dtype == WKV_F32 ? 4 : 2; }
+
 // Per-sequence parameters, passed to kernels by value inside the kernel argument block so
 // that no host-to-device copy (and no allocation) is ever needed for metadata.
 struct SeqParam {

@@ -17,7 +17,7 @@
 // over; pass 1 and the fold are then skipped and the keys are read once.
 //
 // Two kernel families implement the passes:
-//   * MFMA (bf16 inputs, any M <= 256): v_mfma_f32_16x16x32_bf16 with the keys as the A operand,
+//   * MFMA (bf16 or fp16 inputs): v_mfma_f32_16x16x32_bf16 / _f16 with the keys as the A operand,
 //     loaded straight from global memory into registers in operand layout, so K never passes
 //     through LDS and the four waves of a workgroup never synchronise in the loop; the
 //     query rows are the B operand, read as pre-arranged fragments from LDS.
@@ -31,9 +31,6 @@ namespace wkv {
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
-};
-template <> struct Elem<uint16_t> {
-  static __device__ __forceinline__ float load(const void *p, int64_t i) { return bf16_to_float(((const uint16_t *)p)[i]); }
 };
 
 // =========================================================================================
@@ -202,7 +199,7 @@ __global__ __launch_bounds__(GEN_THREADS) void score_generic_kernel(Shape s, Bat
 // row tiles 0..MT-1 and waves 4-7 on row tiles MT..2MT-1 of the same key tiles (the second
 // read of a key tile hits the CU's vector cache), the 64 KB of query fragments allow one
 // workgroup per CU, and pass 2 adds the column sums of the two halves in its epilogue.
-template <int D, int MT, int HV, int PASS>
+template <int D, int MT, int HV, int PASS, bool F16>
 __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_kernel(Shape s, BatchParams bp, GroupPtrs gp,
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    const float *__restrict__ lse_g,
@@ -325,8 +322,7 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
           const bf16x8 qb = *(const bf16x8 *)&qraw;
 #pragma unroll
           for (int n = 0; n < MF_KT; ++n)
-            acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.f[n][ks], qb,
-                                                                  ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[n][mt], 0, 0, 0);
+            acc[n][mt] = mfma_16x16x32<F16>(kf.f[n][ks], qb, ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[n][mt]);
         }
       }
       if (mt > 0) {
@@ -464,7 +460,7 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
 // =========================================================================================
 // launch
 // =========================================================================================
-template <int D, int MT, int HV>
+template <int D, int MT, int HV, bool F16>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                               int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
                               float *s_pool, hipStream_t stream, hipEvent_t mid) {
@@ -475,7 +471,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
     if (s.t_stride <= 0) return hipSuccess;
   } else {
     dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1, F16>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
@@ -487,7 +483,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
   ScorePlan pl2 = pl;
   if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2, F16>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
   return hipGetLastError();
 }
 
@@ -527,20 +523,16 @@ hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &
                         hipStream_t stream, hipEvent_t mid) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
-#define WKV_MFMA_CASE(DD, MM) \
-  if (s.d == DD && mt <= MM) return launch_mfma<DD, MM, 1>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
-    WKV_MFMA_CASE(128, 1) WKV_MFMA_CASE(128, 2) WKV_MFMA_CASE(128, 4) WKV_MFMA_CASE(128, 8)
-    WKV_MFMA_CASE(64, 1) WKV_MFMA_CASE(64, 2) WKV_MFMA_CASE(64, 4) WKV_MFMA_CASE(64, 8)
+    const bool f16 = s.dtype == WKV_F16;
+#define WKV_MFMA_CASE(DD, MM, HH)                                                                              \
+  if (s.d == DD && mt <= MM * HH)                                                                              \
+    return f16 ? launch_mfma<DD, MM, HH, true>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid) \
+               : launch_mfma<DD, MM, HH, false>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
+    WKV_MFMA_CASE(128, 1, 1) WKV_MFMA_CASE(128, 2, 1) WKV_MFMA_CASE(128, 4, 1) WKV_MFMA_CASE(128, 8, 1)
+    WKV_MFMA_CASE(64, 1, 1) WKV_MFMA_CASE(64, 2, 1) WKV_MFMA_CASE(64, 4, 1) WKV_MFMA_CASE(64, 8, 1)
+    WKV_MFMA_CASE(128, 8, 2) WKV_MFMA_CASE(64, 8, 2)      // 129..256 rows: two halves of 8 row tiles
 #undef WKV_MFMA_CASE
-    if (mt <= 16) {                                    // 129..256 rows: two halves of 8 row tiles
-      if (s.d == 128) return launch_mfma<128, 8, 2>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
-      if (s.d == 64) return launch_mfma<64, 8, 2>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
-    }
     return hipErrorInvalidValue;
-  }
-  if (s.dtype == WKV_BF16) {
-    if (s.d == 128) return launch_generic<uint16_t, 128>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
-    return launch_generic<uint16_t, 64>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
   }
   if (s.d == 128) return launch_generic<float, 128>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);
   return launch_generic<float, 64>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, stream, mid);

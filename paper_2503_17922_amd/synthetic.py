@@ -12,22 +12,40 @@ import wkv_synth as S
 
 
 def make_problem(w: S.Workload, **kw) -> W.Problem:
+    kw.setdefault("dtype", W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16)
     return W.Problem(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, w_obs=w.w_obs,
                      seq_len=w.seq_len, win=w.win, top_p=w.top_p, k_windows=w.k_windows,
-                     dtype=W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16, max_seq_len=w.max_seq_len, **kw)
+                     max_seq_len=w.max_seq_len, **kw)
+
+
+def _exact_half(t: torch.Tensor) -> torch.Tensor:
+    """The same values as IEEE half; refuses a tensor that half cannot hold exactly."""
+    h = t.to(torch.float16)
+    assert torch.equal(h.to(torch.float32), t.to(torch.float32)), "values are not representable in fp16"
+    return h
 
 
 class DeviceState:
     """All device tensors of one workload plus the outputs of one wkv_compress_groups call."""
 
-    def __init__(self, w: S.Workload, device, layers=True, flags=0):
+    def __init__(self, w: S.Workload, device, layers=True, flags=0, as_f16=False):
+        """``as_f16``: a bf16 workload handed to the library as IEEE half tensors.  Every value the
+        generator makes in bf16 is exactly representable in fp16, so the inputs (and what the
+        oracle computes from them) are the same numbers in another storage format."""
         self.w = w
         self.device = device
-        self.problem = make_problem(w, flags=flags)
+        self.as_f16 = as_f16
+        kw = dict(dtype=W.WKV_F16) if as_f16 else {}
+        self.problem = make_problem(w, flags=flags, **kw)
         self.dims = W.wkv_get_dims(self.problem)
         self.q = [w.q_obs_torch(g, device) for g in range(w.n_groups)]
         self.k = [w.kv_torch(S.KIND_K, l, device) for l in range(w.n_layers)]
         self.v = [w.kv_torch(S.KIND_V, l, device) for l in range(w.n_layers)]
+        if as_f16:
+            assert w.dtype == "bf16"
+            self.q = [_exact_half(t) for t in self.q]
+            self.k = [_exact_half(t) for t in self.k]
+            self.v = [_exact_half(t) for t in self.v]
         B, H, d = w.batch, w.n_kv_heads, w.head_dim
         nk = self.dims.nkeep_max
         dt = self.k[0].dtype

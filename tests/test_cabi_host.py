@@ -79,6 +79,14 @@ def test_invalid_problems_are_rejected_on_the_host(kw, status):
     assert len(str(e.value)) > 20
 
 
+def test_half_precision_dtypes_share_limits_and_sizes():
+    a, b = W.wkv_get_dims(_problem(dtype=W.WKV_F16)), W.wkv_get_dims(_problem(dtype=W.WKV_BF16))
+    assert (a.obs_rows, a.nw_max, a.k_max, a.nkeep_max) == (b.obs_rows, b.nw_max, b.k_max, b.nkeep_max)
+    assert W.wkv_workspace_bytes(_problem(dtype=W.WKV_F16), 3) == W.wkv_workspace_bytes(_problem(dtype=W.WKV_BF16), 3)
+    with pytest.raises(W.WkvError):                      # rows of 2-byte elements need strides in units of 8
+        W.wkv_get_dims(_problem(dtype=W.WKV_F16, kv_strides=(8 * 4096 * 132, 4096 * 132, 132)))
+
+
 def test_known_flags_are_accepted():
     assert W.wkv_get_dims(_problem(flags=W.WKV_KEEP_PADDING)).nkeep_max == W.wkv_get_dims(_problem()).nkeep_max
 

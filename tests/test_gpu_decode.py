@@ -17,21 +17,22 @@ RTOL, ATOL = 1e-3, 2e-5     # fp32 accumulation and a hardware exp2 against fp64
 KIND_DECODE = 9             # generator stream of the new-token tensors
 
 
-def _new_token(w, device, step, what, shape):
+def _new_token(w, device, step, what, shape, as_f16=False):
     numel = int(np.prod(shape))
-    return S.normal_torch(w.seed, S.stream_id(KIND_DECODE, step, what), numel, w.dtype, device).view(*shape)
+    t = S.normal_torch(w.seed, S.stream_id(KIND_DECODE, step, what), numel, w.dtype, device).view(*shape)
+    return t.to(torch.float16) if as_f16 else t          # exact: see DeviceState(as_f16=True)
 
 
-def _decode_and_check(w, device, n_steps, extra_rows):
+def _decode_and_check(w, device, n_steps, extra_rows, as_f16=False):
     """Compress a workload straight into caches with room for ``extra_rows`` more tokens, then
     generate ``n_steps`` tokens on the first layer and follow every step with the oracle."""
     base = P.make_problem(w)
     nk = W.wkv_get_dims(base).nkeep_max
     cap = nk + extra_rows
     B, H, Hq, d, G = w.batch, w.n_kv_heads, w.n_q_heads, w.head_dim, w.q_per_kv
-    st = P.DeviceState(w, device)
+    st = P.DeviceState(w, device, as_f16=as_f16)
     # the compact caches ARE the decode caches: same tensors, strides for `cap` rows
-    st.problem = P.make_problem(w, out_strides=(H * cap * d, cap * d, d))
+    st.problem = P.make_problem(w, out_strides=(H * cap * d, cap * d, d), **(dict(dtype=W.WKV_F16) if as_f16 else {}))
     dt = st.k[0].dtype
     st.k_out = [torch.full((B, H, cap, d), 7.0, dtype=dt, device=device) for _ in range(w.n_layers)]
     st.v_out = [torch.full((B, H, cap, d), 7.0, dtype=dt, device=device) for _ in range(w.n_layers)]
@@ -39,7 +40,7 @@ def _decode_and_check(w, device, n_steps, extra_rows):
     layer, g = 0, 0
     n_valid = st.n_keep[g].clone()                                   # [B, H]
     shape = W.DecodeShape(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, capacity=cap,
-                          dtype=W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16)
+                          dtype=W.WKV_F16 if as_f16 else (W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16))
     ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
     out = torch.full((B, Hq, d), -5.0, dtype=torch.float32, device=device)
     # oracle state: the retained rows of every (b, h), widened exactly
@@ -47,9 +48,9 @@ def _decode_and_check(w, device, n_steps, extra_rows):
     ok = {(b, h): P.host_f64(w, st.k_out[layer][b, h, : n0[b, h]]) for b in range(B) for h in range(H)}
     ov = {(b, h): P.host_f64(w, st.v_out[layer][b, h, : n0[b, h]]) for b in range(B) for h in range(H)}
     for step in range(n_steps):
-        q = _new_token(w, device, step, 0, (B, Hq, d))
-        kn = _new_token(w, device, step, 1, (B, H, d))
-        vn = _new_token(w, device, step, 2, (B, H, d))
+        q = _new_token(w, device, step, 0, (B, Hq, d), as_f16)
+        kn = _new_token(w, device, step, 1, (B, H, d), as_f16)
+        vn = _new_token(w, device, step, 2, (B, H, d), as_f16)
         k_before, v_before = st.k_out[layer].clone(), st.v_out[layer].clone()
         W.wkv_decode_step(shape, q, kn, vn, st.k_out[layer], st.v_out[layer], n_valid, out, ws)
         torch.cuda.synchronize()
@@ -98,6 +99,18 @@ def test_decode_shapes(device, kw):
                 w_obs=16, seq_len=[700], win=[8], top_p=[8], k_windows=[30])
     base.update(kw)
     _decode_and_check(S.Workload(**base), device, n_steps=2, extra_rows=5)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                                                             # G = 4, d = 128
+    dict(head_dim=64, n_q_heads=14, n_kv_heads=2, w_obs=8),                             # G = 7, d = 64
+])
+def test_decode_fp16(device, kw):
+    # IEEE half caches: the same values as the bf16 workload (exactly representable), another format
+    base = dict(name="dec_f16", seed=95, dtype="bf16", n_groups=1, gamma=1, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                w_obs=16, seq_len=[900, 300], win=[8, 16], top_p=[8, 8], k_windows=[30, 6])
+    base.update(kw)
+    _decode_and_check(S.Workload(**base), device, n_steps=3, extra_rows=8, as_f16=True)
 
 
 def test_decode_full_cache_is_refused_per_row(device):

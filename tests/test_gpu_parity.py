@@ -23,18 +23,19 @@ def _sample(items, n, seed):
     return [items[i] for i in sorted(pick)]
 
 
-def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check_stage_group=0):
+def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check_stage_group=0, as_f16=False):
     """One wkv_compress_groups call checked against the oracle.
 
     n_oracle: how many (group, b, h) problems the oracle recomputes (None = all).
     n_gather_cpu: how many (layer, K|V, b, h) slices are compared on the CPU with the oracle's
     gather (None = all); every slice is additionally compared on the device.
     """
-    st = P.DeviceState(w, device)
+    st = P.DeviceState(w, device, as_f16=as_f16)
     print(f"[{w.name}] L={w.seq_len} win={w.win} p={w.top_p} k={w.k_windows} groups={w.n_groups}x{w.gamma} "
           f"ws={st.ws_bytes >> 10} KiB", flush=True)
-    P.check_generator_matches(w, S.KIND_K, 0, st.k[0], 0, 0)
-    P.check_generator_matches(w, S.KIND_V, w.n_layers - 1, st.v[-1], w.batch - 1, w.n_kv_heads - 1)
+    if not as_f16:
+        P.check_generator_matches(w, S.KIND_K, 0, st.k[0], 0, 0)
+        P.check_generator_matches(w, S.KIND_V, w.n_layers - 1, st.v[-1], w.batch - 1, w.n_kv_heads - 1)
     k_before = st.k[0][0, 0, : min(64, w.seq_len[0])].clone()
     st.compress()
     assert torch.equal(k_before, st.k[0][0, 0, : min(64, w.seq_len[0])]), "inputs were modified"
@@ -213,6 +214,22 @@ def _random_workload(i):
 @pytest.mark.parametrize("i", range(24))
 def test_random_shapes(i, device):
     run_and_check(_random_workload(i), device)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                                               # 128 rows, ragged tail
+    dict(seq_len=[1000, 16, 333, 2048], win=[8, 8, 32, 128], top_p=[4, 8, 1, 64], k_windows=[20, 0, 3, 5]),
+    dict(head_dim=64, seq_len=[3000], k_windows=[40]),
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[1500]),           # 256 rows
+    dict(n_q_heads=6, n_kv_heads=2, w_obs=5),                             # 15 rows
+])
+def test_fp16_inputs(kw, device):
+    # IEEE half tensors holding the values of the bf16 workload (all exactly representable)
+    run_and_check(_mini(**kw), device, as_f16=True)
+
+
+def test_fp16_config_c2(device):
+    run_and_check(S.make_workload("c2"), device, as_f16=True)
 
 
 def test_large_logits_are_stable(device):
