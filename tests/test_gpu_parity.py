@@ -472,6 +472,27 @@ def test_window_pool_alone(device):
             np.testing.assert_allclose(s_dev[0, h].cpu().numpy(), want, rtol=2e-6)
 
 
+def test_profiled_call_gives_the_same_results_and_sane_times(device):
+    w = _mini(seq_len=[1500, 700], win=[8, 16], top_p=[8, 5], k_windows=[40, 9], n_groups=2, gamma=2)
+    ref = P.DeviceState(w, device); ref.compress()
+    st = P.DeviceState(w, device)
+    call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, None, st.k, st.v, st.k_out, st.v_out,
+                          st.win_idx, st.tok_idx, st.n_keep, st.workspace)
+    ms = call.profiled()
+    torch.cuda.synchronize()
+    assert len(ms) == W.WKV_N_STAGES == len(W.STAGE_NAMES)
+    assert all(0.0 <= x < 50.0 for x in ms) and ms[0] > 0.0 and ms[1] > 0.0 and ms[4] > 0.0, ms
+    for a, b in zip((st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out),
+                    (ref.win_idx, ref.tok_idx, ref.n_keep, *ref.k_out, *ref.v_out)):
+        assert torch.equal(a, b)
+    # with the normalisers handed over there is no statistics pass: its slot reads 0
+    lse = [st.oracle_lse(g) for g in range(w.n_groups)]
+    call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, lse, st.k, st.v, st.k_out, st.v_out,
+                          st.win_idx, st.tok_idx, st.n_keep, st.workspace)
+    ms = call.profiled()
+    assert ms[0] < 0.02 and ms[1] > 0.0, ms
+
+
 def test_graph_capture_and_replay(device):
     # The batched call is plain kernel launches on the caller's stream (no allocation, no host
     # synchronisation, no memset nodes), so it can be captured into a HIP graph.  Replays with the
