@@ -249,6 +249,31 @@ def test_large_logits_are_stable(device):
         P.check_selection(s, sel, st.win_idx[0, 0, h, : w.k_windows[0]].cpu().numpy(), w.k_windows[0], f"h{h}")
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling"])
+def test_logit_scale_ramps_along_the_sequence(direction, device):
+    # keys scaled by a factor that runs from 1 to 64 along the sequence (or back): the running
+    # reference of the statistics pass is re-referenced many times (rising) or stays far above the
+    # later logits (falling); several chunks per row, 128 and 256 softmax rows
+    for heads in (8, 16):
+        w = _mini(n_q_heads=heads, n_kv_heads=2, w_obs=32, seq_len=[6000], k_windows=[20], n_groups=1, gamma=1)
+        st = P.DeviceState(w, device)
+        L = w.seq_len[0]
+        ramp = torch.linspace(0.0, 6.0, L, device=device).exp2()            # 1 .. 64
+        if direction == "falling":
+            ramp = ramp.flip(0)
+        st.k[0] = (st.k[0].float() * ramp.view(1, 1, L, 1)).to(st.k[0].dtype)
+        st.compress()
+        t_dev, s_dev, *_ = st.stages(0)
+        assert torch.isfinite(t_dev).all()
+        for h in range(w.n_kv_heads):
+            t, s, sel, idx = P.oracle_problem(w, st.q[0], st.k[0], 0, h)
+            got = t_dev[0, h, : len(t)].cpu().numpy().astype(np.float64)
+            big = t > 1e-6 * t.max()
+            P.assert_scores_close(got[big], t[big], f"{direction} ramp, {heads} heads, h{h}")
+            assert np.all(got[~big] <= 2e-6 * t.max())
+            P.check_selection(s, sel, st.win_idx[0, 0, h, : w.k_windows[0]].cpu().numpy(), w.k_windows[0], f"h{h}")
+
+
 def test_strided_layout(device):
     # K/V stored [B, L, Hkv, d] (token-major), q [B, w_obs, Hq, d], compact cache [B, n, Hkv, d]
     w = _mini(seq_len=[1234, 600], win=[8, 8], top_p=[8, 3], k_windows=[17, 9], n_groups=1, gamma=2)
