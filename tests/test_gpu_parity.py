@@ -190,6 +190,22 @@ def test_edge_cases(kw, device):
     run_and_check(_mini(**kw), device)
 
 
+def test_largest_batch(device):
+    # 64 sequences in one call (the library's limit), lengths 16 .. 646, alternating task modes
+    B = W.WKV_MAX_BATCH
+    seq_len = [16 + 10 * b for b in range(B)]
+    win = [8 if b % 2 else 16 for b in range(B)]
+    top_p = [8 if b % 2 else 5 for b in range(B)]
+    k = [min((seq_len[b] - 16) // win[b], 1 + b % 7) for b in range(B)]
+    w = S.Workload(name="b64", seed=1064, dtype="bf16", n_groups=2, gamma=1, n_q_heads=4, n_kv_heads=2, head_dim=64,
+                   w_obs=16, seq_len=seq_len, win=win, top_p=top_p, k_windows=k)
+    run_and_check(w, device)
+    with pytest.raises(W.WkvError) as e:
+        W.wkv_get_dims(P.make_problem(S.scaled_workload(w, seq_len=seq_len + [100], win=win + [8], top_p=top_p + [8],
+                                                        k_windows=k + [1])))
+    assert e.value.status == W.WKV_ERR_UNSUPPORTED
+
+
 def _random_workload(i):
     """A seeded draw from the supported shape space (small enough for the oracle)."""
     rng = np.random.default_rng(4242 + i)
