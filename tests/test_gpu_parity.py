@@ -461,6 +461,38 @@ def test_keep_padding_flag(device):
             assert torch.equal(v_out[l][b, h, :n], ref.v_out[l][b, h, :n]) and bool((v_out[l][b, h, n:] == 3.0).all())
 
 
+def test_largest_group_count_with_budgets_of_their_own(device):
+    # 64 groups of one layer (the library's limits for groups and layers), 16 sequences: 1024
+    # (group, sequence) budgets, the size of the kernel-argument table
+    n_groups, B = W.WKV_MAX_GROUPS, 16
+    seq_len = [40 + 23 * b for b in range(B)]
+    win = [4] * B
+    nw = [-(-(L - 8) // 4) for L in seq_len]
+    k_groups = [[(g * 7 + b * 3) % (nw[b] + 1) for b in range(B)] for g in range(n_groups)]
+    cap = [max(k_groups[g][b] for g in range(n_groups)) for b in range(B)]
+    w = S.Workload(name="g64", seed=1065, dtype="bf16", n_groups=n_groups, gamma=1, n_q_heads=2, n_kv_heads=1, head_dim=64,
+                   w_obs=8, seq_len=seq_len, win=win, top_p=[3] * B, k_windows=cap)
+    st = P.DeviceState(w, device)
+    st.compress(k_groups=k_groups)
+    win_idx = st.win_idx.cpu().numpy(); tok = st.tok_idx.cpu().numpy(); nkeep = st.n_keep.cpu().numpy()
+    for g, b in itertools.product(range(n_groups), range(B)):
+        k, L = k_groups[g][b], seq_len[b]
+        what = f"g{g} b{b}"
+        t, s, sel, idx = O.select_indices(P.host_f64(w, st.q[g][b, 0:2]), P.host_f64(w, st.k[g][b, 0, :L]), 4, 3, k)
+        assert np.all(win_idx[g, b, 0, k:] == -1), what
+        if P.check_selection(s, sel, win_idx[g, b, 0, :k], k, what):
+            assert np.array_equal(tok[g, b, 0, : len(idx)], idx), what
+        n = int(nkeep[g, b, 0])
+        assert n == len(O.token_indices(win_idx[g, b, 0, :k], 4, L, 8)), what
+        rows = torch.from_numpy(tok[g, b, 0, :n].astype(np.int64)).to(device)
+        assert torch.equal(st.k_out[g][b, 0, :n], st.k[g][b, 0].index_select(0, rows)), what
+        assert torch.equal(st.v_out[g][b, 0, :n], st.v[g][b, 0].index_select(0, rows)), what
+    with pytest.raises(W.WkvError):          # one sequence more would not fit the budget table
+        w2 = S.scaled_workload(w, seq_len=seq_len + [50], win=[4] * 17, top_p=[3] * 17, k_windows=cap + [1])
+        st2 = P.DeviceState(w2, device)
+        st2.compress(k_groups=[row + [0] for row in k_groups])
+
+
 def test_other_layers_do_not_influence_indices(device):
     w = _mini(seq_len=[900], n_groups=1, gamma=3)
     st = P.DeviceState(w, device)
