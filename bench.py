@@ -53,7 +53,7 @@ def algorithmic_bytes(w):
     """Bytes each kernel must move per launch (what the method needs, not what a kernel happens
     to read).  For the whole path the key stream of the scored layers is charged ONCE, although
     the two score kernels each read it: the second read is this implementation's cost."""
-    e = 2 if w.dtype == "bf16" else 4
+    e = 4 if w.dtype == "f32" else 2
     d, H = w.head_dim, w.n_kv_heads
     row = d * e
     k_first = sum(w.seq_len) * H * row * w.n_groups                      # K of each scored layer, once

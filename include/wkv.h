@@ -21,7 +21,8 @@
  *     during the call only and may be freed on return.
  *   - Work is enqueued on the caller's hipStream_t (passed as void*; NULL = default stream).
  *     Calls return without synchronising; results are valid in stream order.
- *   - The library allocates nothing, frees nothing and keeps no device state between calls.
+ *   - The library allocates nothing, frees nothing and keeps no device state between calls (its
+ *     only state is the calling thread's last error message, see wkv_last_error).
  *     Every call except wkv_compress_groups_profiled is a fixed sequence of kernel launches on
  *     the stream (no memset or copy nodes, no host synchronisation), so it can be captured into
  *     a HIP graph; host arrays are read at capture time.
@@ -113,6 +114,26 @@ wkv_status wkv_get_dims(const wkv_problem *problem, wkv_dims *dims);
 size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups);
 
 /*
+ * Diagnostic (host only): where wkv_compress_groups leaves the intermediate results of Eq. 2
+ * and Eq. 3-4 inside the caller's workspace, so that a test can compare them element by element.
+ *   t_offset   byte offset of the token scores  float32 [n_groups, batch, n_kv_heads, t_stride]
+ *   s_offset   byte offset of the window scores float32 [n_groups, batch, n_kv_heads, nw_max]
+ *   t_written  1 if the batched call writes the token scores to memory for this problem; 0 when
+ *              its score kernel pools them on chip (every window size divides 128, 16-bit
+ *              inputs) and they never leave the compute unit
+ *   s_written  1 if the batched call writes the window scores to memory (entries w < NW_b of
+ *              each row; the rest of a row is unspecified); 0 when pooling happens inside its
+ *              selection kernel
+ * Exactly one of t_written / s_written is 1.  The stage calls do not use these regions.
+ */
+typedef struct {
+  size_t t_offset, s_offset;
+  int32_t t_written, s_written;
+} wkv_workspace_layout;
+wkv_status wkv_get_workspace_layout(const wkv_problem *problem, int32_t n_groups,
+                                    wkv_workspace_layout *layout);
+
+/*
  * Eq. 1-2: token scores of one layer group.
  *   q_obs   device, layout above
  *   k_first device, K of the group's first layer
@@ -173,6 +194,27 @@ wkv_status wkv_gather_group(const wkv_problem *problem, int32_t n_layers,
                             const int32_t *tok_idx, const int32_t *n_keep,
                             void *const *k_out_layers, void *const *v_out_layers,
                             void *hip_stream);
+
+/*
+ * Section 2.2 for ONE layer group of gamma layers: Eq. 1-4 and the selection (2.2.1) on the
+ * group's first layer, then every layer of the group keeps the rows at the shared indices
+ * (2.2.2).  The same results as wkv_score, wkv_window_pool, wkv_topk_windows and
+ * wkv_gather_group called in turn; a thin wrapper over wkv_compress_groups with n_groups = 1.
+ *   q_obs, lse_obs         device, as at wkv_score (lse_obs may be NULL)
+ *   k_layers, v_layers,
+ *   k_out_layers,
+ *   v_out_layers           host arrays [gamma] of device pointers; k_layers[0] is scored
+ *   win_idx_out            device int32 [batch, n_kv_heads, k_max]
+ *   tok_idx_out            device int32 [batch, n_kv_heads, nkeep_max]
+ *   n_keep_out             device int32 [batch, n_kv_heads]
+ *   workspace              wkv_workspace_bytes(problem, 1) bytes
+ */
+wkv_status wkv_compress_group(const wkv_problem *problem, int32_t gamma, const void *q_obs,
+                              const float *lse_obs, const void *const *k_layers,
+                              const void *const *v_layers, void *const *k_out_layers,
+                              void *const *v_out_layers, int32_t *win_idx_out,
+                              int32_t *tok_idx_out, int32_t *n_keep_out, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
 
 /*
  * The whole path (Eq. 1-4, selection, sharing, gather) for n_groups layer groups of gamma
@@ -249,6 +291,13 @@ wkv_status wkv_group_budgets(double b_total, int32_t n_groups, double lambda,
 wkv_status wkv_index_jaccard(const wkv_problem *problem, int32_t n_sets, const int32_t *tok_idx,
                              const int32_t *n_keep, float *jaccard_out, void *hip_stream);
 
+/* wkv_decode_shape.flags.  The gamma layers of a group share one index set (Section 2.2.2), hence
+ * one n_keep row per (sequence, KV head): a caller that keeps ONE row counter per group runs the
+ * decode step of the group's first gamma-1 layers with WKV_DECODE_KEEP_COUNT (the counter is read
+ * but not changed) and the last layer's without it (the counter advances once per token).  A
+ * caller with a counter per layer never sets it. */
+#define WKV_DECODE_KEEP_COUNT 1
+
 /*
  * Generation over the compact cache (what the throughput test of Section 3.5 runs): one decode
  * step of one layer.  For every (sequence b, KV head h) with n = n_valid[b,h] retained rows, the
@@ -266,6 +315,7 @@ typedef struct {
   float   scale;            /* logit scale; 0 selects 1/sqrt(head_dim)                         */
   int32_t capacity;         /* token rows per (b, h) in the caches (nkeep_max + tokens to come) */
   int64_t cache_stride_b, cache_stride_h, cache_stride_t;   /* elements; head_dim contiguous   */
+  int32_t flags;            /* 0, or WKV_DECODE_KEEP_COUNT                                     */
 } wkv_decode_shape;
 
 /* Bytes of 256-byte-aligned device workspace wkv_decode_step needs; 0 for an invalid shape. */
@@ -277,8 +327,12 @@ size_t wkv_decode_workspace_bytes(const wkv_decode_shape *shape);
  *   k_cache,
  *   v_cache        device [batch, n_kv_heads, capacity, head_dim] by the strides above; rows
  *                  0 .. n_valid[b,h]-1 are read, row n_valid[b,h] is written
- *   n_valid        device int32 [batch, n_kv_heads]; read, then incremented by one (the n_keep
- *                  array of the compression calls can be passed as it is)
+ *   n_valid        device int32 [batch, n_kv_heads]; read, then incremented by one unless
+ *                  WKV_DECODE_KEEP_COUNT is set.  It counts the rows of THIS layer's caches: the
+ *                  n_keep row of a group describes all gamma layers of the group, so pass either a
+ *                  copy per layer, or the shared row with WKV_DECODE_KEEP_COUNT on all but the
+ *                  group's last layer (otherwise the second layer would find the counter already
+ *                  advanced and attend to a row its cache does not hold yet)
  *   out            device float32 [batch, n_q_heads, head_dim]
  * A (b, h) whose n_valid is negative or already equals capacity cannot take the new row: its
  * caches and n_valid are left untouched and its rows of `out` are set to NaN.

@@ -17,14 +17,16 @@ LIB_PATH = os.path.join(_HERE, "libwkv.so")
 WKV_OK, WKV_ERR_INVALID_ARG, WKV_ERR_UNSUPPORTED, WKV_ERR_WORKSPACE, WKV_ERR_HIP = 0, -1, -2, -3, -4
 WKV_F32, WKV_BF16, WKV_F16 = 0, 1, 2
 WKV_KEEP_PADDING = 1          # Problem(flags=...): leave compact-cache rows past n_keep untouched
+WKV_DECODE_KEEP_COUNT = 1     # DecodeShape(flags=...): n_valid is read but not advanced
 WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
 WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768
 WKV_N_STAGES = 5
 STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
 
-EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_score", "wkv_window_pool", "wkv_topk_windows",
-           "wkv_gather_group", "wkv_compress_groups", "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string",
-           "wkv_last_error", "wkv_decode_workspace_bytes", "wkv_decode_step", "wkv_index_jaccard")
+EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_get_workspace_layout", "wkv_score", "wkv_window_pool",
+           "wkv_topk_windows", "wkv_gather_group", "wkv_compress_group", "wkv_compress_groups",
+           "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string", "wkv_last_error",
+           "wkv_decode_workspace_bytes", "wkv_decode_step", "wkv_index_jaccard")
 
 
 class WkvError(RuntimeError):
@@ -50,12 +52,17 @@ class _Problem(C.Structure):
 class _DecodeShape(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("scale", C.c_float), ("capacity", C.c_int32),
-                ("cache_stride_b", C.c_int64), ("cache_stride_h", C.c_int64), ("cache_stride_t", C.c_int64)]
+                ("cache_stride_b", C.c_int64), ("cache_stride_h", C.c_int64), ("cache_stride_t", C.c_int64),
+                ("flags", C.c_int32)]
 
 
 class Dims(C.Structure):
     _fields_ = [("obs_rows", C.c_int32), ("t_stride", C.c_int32), ("nw_max", C.c_int32),
                 ("k_max", C.c_int32), ("nkeep_max", C.c_int32), ("total_tokens", C.c_int64)]
+
+
+class WorkspaceLayout(C.Structure):
+    _fields_ = [("t_offset", C.c_size_t), ("s_offset", C.c_size_t), ("t_written", C.c_int32), ("s_written", C.c_int32)]
 
 
 _lib = None
@@ -73,6 +80,8 @@ def lib() -> C.CDLL:
     P, VP = C.POINTER(_Problem), C.c_void_p
     l.wkv_get_dims.argtypes = [P, C.POINTER(Dims)]; l.wkv_get_dims.restype = C.c_int
     l.wkv_workspace_bytes.argtypes = [P, C.c_int32]; l.wkv_workspace_bytes.restype = C.c_size_t
+    l.wkv_get_workspace_layout.argtypes = [P, C.c_int32, C.POINTER(WorkspaceLayout)]
+    l.wkv_get_workspace_layout.restype = C.c_int
     l.wkv_score.argtypes = [P, VP, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_score.restype = C.c_int
     l.wkv_window_pool.argtypes = [P, VP, VP, VP]; l.wkv_window_pool.restype = C.c_int
     l.wkv_topk_windows.argtypes = [P, VP, VP, VP, VP, VP]; l.wkv_topk_windows.restype = C.c_int
@@ -83,6 +92,9 @@ def lib() -> C.CDLL:
                                       C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), VP, VP, VP, VP,
                                       C.c_size_t, VP]
     l.wkv_compress_groups.restype = C.c_int
+    l.wkv_compress_group.argtypes = [P, C.c_int32, VP, VP, C.POINTER(VP), C.POINTER(VP), C.POINTER(VP), C.POINTER(VP),
+                                     VP, VP, VP, VP, C.c_size_t, VP]
+    l.wkv_compress_group.restype = C.c_int
     l.wkv_compress_groups_profiled.argtypes = l.wkv_compress_groups.argtypes + [C.POINTER(C.c_float)]
     l.wkv_compress_groups_profiled.restype = C.c_int
     l.wkv_group_budgets.argtypes = [C.c_double, C.c_int32, C.c_double, C.POINTER(C.c_double)]
@@ -121,15 +133,21 @@ class Problem:
         self._keep = [_i32(seq_len), _i32(win), _i32(top_p), _i32(k_windows)]
         if max_seq_len is None:
             max_seq_len = max(seq_len) if B else 0
-        if nkeep_max is None:
-            nkeep_max = max([k * w for k, w in zip(k_windows, win)], default=0) + w_obs
         d = head_dim
         q_strides = q_strides or (n_q_heads * w_obs * d, w_obs * d, d)
         kv_strides = kv_strides or (n_kv_heads * max_seq_len * d, max_seq_len * d, d)
-        out_strides = out_strides or (n_kv_heads * nkeep_max * d, nkeep_max * d, d)
+        # contiguous compact caches have nkeep_max rows per head; that size is the library's to derive
+        # (wkv_get_dims), so the strides start from a placeholder and are set once it is known
         self.c = _Problem(B, n_q_heads, n_kv_heads, head_dim, w_obs, max_seq_len, dtype, scale,
                           self._keep[0], self._keep[1], self._keep[2], self._keep[3],
-                          *q_strides, *kv_strides, *out_strides, flags)
+                          *q_strides, *kv_strides, *(out_strides or (d, d, d)), flags)
+        if out_strides is None:
+            if nkeep_max is None:
+                dims = Dims()
+                if lib().wkv_get_dims(C.byref(self.c), C.byref(dims)) == WKV_OK:
+                    nkeep_max = dims.nkeep_max
+            if nkeep_max is not None:      # an invalid problem keeps the placeholder; every call rejects it anyway
+                self.c.out_stride_b, self.c.out_stride_h, self.c.out_stride_t = n_kv_heads * nkeep_max * d, nkeep_max * d, d
 
     def ref(self):
         return C.byref(self.c)
@@ -161,6 +179,12 @@ def wkv_workspace_bytes(problem: Problem, n_groups: int = 1) -> int:
     if n == 0:
         raise WkvError(WKV_ERR_INVALID_ARG, lib().wkv_last_error().decode())
     return int(n)
+
+
+def wkv_get_workspace_layout(problem: Problem, n_groups: int = 1) -> WorkspaceLayout:
+    lay = WorkspaceLayout()
+    _check(lib().wkv_get_workspace_layout(problem.ref(), n_groups, C.byref(lay)))
+    return lay
 
 
 def wkv_score(problem, q_obs, k_first, lse_obs, t_out, workspace, stream=None) -> None:
@@ -225,6 +249,15 @@ def wkv_compress_groups(problem, n_groups, gamma, q_obs_groups, lse_obs_groups, 
                  v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, k_windows_groups)(stream)
 
 
+def wkv_compress_group(problem, gamma, q_obs, lse_obs, k_layers, v_layers, k_out_layers, v_out_layers, win_idx_out,
+                       tok_idx_out, n_keep_out, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().wkv_compress_group(problem.ref(), gamma, _ptr(q_obs), _ptr(lse_obs), _ptr_array(k_layers),
+                                    _ptr_array(v_layers), _ptr_array(k_out_layers), _ptr_array(v_out_layers),
+                                    _ptr(win_idx_out), _ptr(tok_idx_out), _ptr(n_keep_out), _ptr(workspace), ws_bytes,
+                                    _stream(stream)))
+
+
 def wkv_index_jaccard(problem, n_sets, tok_idx, n_keep, jaccard_out, stream=None) -> None:
     _check(lib().wkv_index_jaccard(problem.ref(), n_sets, _ptr(tok_idx), _ptr(n_keep), _ptr(jaccard_out), _stream(stream)))
 
@@ -234,9 +267,9 @@ class DecodeShape:
     ``[B, Hkv, capacity, d]`` caches."""
 
     def __init__(self, *, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, capacity: int,
-                 scale: float = 0.0, cache_strides=None):
+                 scale: float = 0.0, cache_strides=None, flags: int = 0):
         cache_strides = cache_strides or (n_kv_heads * capacity * head_dim, capacity * head_dim, head_dim)
-        self.c = _DecodeShape(batch, n_q_heads, n_kv_heads, head_dim, dtype, scale, capacity, *cache_strides)
+        self.c = _DecodeShape(batch, n_q_heads, n_kv_heads, head_dim, dtype, scale, capacity, *cache_strides, flags)
 
     def ref(self):
         return C.byref(self.c)

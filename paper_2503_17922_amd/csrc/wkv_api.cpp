@@ -216,6 +216,17 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
                        nullptr);
 }
 
+wkv_status wkv_compress_group(const wkv_problem *problem, int32_t gamma, const void *q_obs, const float *lse_obs,
+                              const void *const *k_layers, const void *const *v_layers, void *const *k_out_layers,
+                              void *const *v_out_layers, int32_t *win_idx_out, int32_t *tok_idx_out,
+                              int32_t *n_keep_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  const void *q_groups[1] = {q_obs};
+  const float *lse_groups[1] = {lse_obs};
+  return compress_impl(problem, 1, gamma, q_groups, lse_obs ? lse_groups : nullptr, nullptr, k_layers, v_layers,
+                       k_out_layers, v_out_layers, win_idx_out, tok_idx_out, n_keep_out, workspace, workspace_bytes,
+                       hip_stream, nullptr);
+}
+
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                         const void *const *q_obs_groups, const float *const *lse_obs_groups,
                                         const int32_t *k_windows_groups, const void *const *k_layers,

@@ -452,7 +452,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_combine_kernel(DecodeShape
   }
   if (threadIdx.x == 0) {
     const int n = n_valid[bh];
-    if (n >= 0 && n < s.capacity) n_valid[bh] = n + 1;
+    if (n >= 0 && n < s.capacity && !s.keep_count) n_valid[bh] = n + 1;
   }
 }
 

@@ -178,12 +178,14 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_group
   const size_t tb = align256(rows * (size_t)(s.t_stride > 0 ? s.t_stride : 1) * sizeof(float));
   const size_t sb = align256(rows * (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(float));
   const size_t lb = align256(rows * plan.m_pad * sizeof(float));
-  char *b = (char *)base;
-  w.partials = (float2 *)b;
-  w.t = (float *)(b + part);
-  w.s = (float *)(b + part + tb);
-  w.lse = (float *)(b + part + tb + sb);
+  w.t_offset = part;
+  w.s_offset = part + tb;
   w.bytes = part + tb + sb + lb;
+  char *b = (char *)base;          // a null base asks for the sizes only: no pointer is formed from it
+  w.partials = b ? (float2 *)b : nullptr;
+  w.t = b ? (float *)(b + w.t_offset) : nullptr;
+  w.s = b ? (float *)(b + w.s_offset) : nullptr;
+  w.lse = b ? (float *)(b + part + tb + sb) : nullptr;
   return w;
 }
 
@@ -208,6 +210,7 @@ wkv_status validate_decode(const wkv_decode_shape *p, Decode *out) {
     set_error("scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))"); return WKV_ERR_INVALID_ARG;
   }
   if (p->capacity < 1) { set_error("capacity must be >= 1"); return WKV_ERR_INVALID_ARG; }
+  if (p->flags & ~WKV_DECODE_KEEP_COUNT) { set_error("unknown bits in flags (0x%x)", p->flags); return WKV_ERR_INVALID_ARG; }
   const int64_t vec = 16 / elem_bytes(p->dtype);
   const int64_t strides[3] = {p->cache_stride_b, p->cache_stride_h, p->cache_stride_t};
   for (int i = 0; i < 3; ++i)
@@ -221,6 +224,7 @@ wkv_status validate_decode(const wkv_decode_shape *p, Decode *out) {
   DecodeShape &s = out->shape;
   s.B = p->batch; s.Hq = p->n_q_heads; s.Hkv = p->n_kv_heads; s.d = p->head_dim; s.G = G; s.dtype = p->dtype;
   s.capacity = p->capacity;
+  s.keep_count = (p->flags & WKV_DECODE_KEEP_COUNT) ? 1 : 0;
   const double scale = p->scale > 0.0f ? (double)p->scale : 1.0 / std::sqrt((double)p->head_dim);
   s.c1 = (float)(scale * 1.4426950408889634074);
   s.sb = p->cache_stride_b; s.sh = p->cache_stride_h; s.st = p->cache_stride_t;
@@ -253,6 +257,23 @@ size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups) {
   fill_shape(problem, dm, &s, &bp);
   ScorePlan pl = plan_score(s, bp, n_groups);
   return carve_workspace(s, pl, n_groups, nullptr).bytes;
+}
+
+wkv_status wkv_get_workspace_layout(const wkv_problem *problem, int32_t n_groups, wkv_workspace_layout *layout) {
+  if (!layout) { set_error("layout is NULL"); return WKV_ERR_INVALID_ARG; }
+  wkv_dims dm;
+  wkv_status st = validate(problem, &dm);
+  if (st != WKV_OK) return st;
+  if (n_groups < 1 || n_groups > WKV_MAX_GROUPS) { set_error("n_groups outside [1, %d]", WKV_MAX_GROUPS); return WKV_ERR_INVALID_ARG; }
+  Shape s; BatchParams bp;
+  fill_shape(problem, dm, &s, &bp);
+  const ScorePlan pl = plan_score(s, bp, n_groups);
+  const Workspace w = carve_workspace(s, pl, n_groups, nullptr);
+  layout->t_offset = w.t_offset;
+  layout->s_offset = w.s_offset;
+  layout->s_written = pl.pool_in_pass2 ? 1 : 0;
+  layout->t_written = pl.pool_in_pass2 ? 0 : 1;
+  return WKV_OK;
 }
 
 size_t wkv_decode_workspace_bytes(const wkv_decode_shape *shape) {

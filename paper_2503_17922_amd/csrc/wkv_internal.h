@@ -78,6 +78,7 @@ struct Workspace {
   float *lse;         // [n_groups][B][Hkv][m_pad] base-2 log-sum-exp of every softmax row
   float *t;           // [n_groups][B][Hkv][t_stride]
   float *s;           // [n_groups][B][Hkv][nw_max]
+  size_t t_offset, s_offset;   // byte offsets of t and s from the base
   size_t bytes;
 };
 
@@ -112,6 +113,7 @@ struct DecodeShape {
   int32_t B, Hq, Hkv, d, G, dtype;
   int32_t capacity;          // token rows per (sequence, KV head) in the caches
   int32_t n_splits, chunk;   // key ranges per (sequence, KV head) and their length
+  int32_t keep_count;        // leave n_valid as it is (the caller advances it after the group's last layer)
   float c1;                  // scale * log2(e)
   int64_t sb, sh, st;        // cache strides in elements
 };

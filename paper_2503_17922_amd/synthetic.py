@@ -12,7 +12,7 @@ import wkv_synth as S
 
 
 def make_problem(w: S.Workload, **kw) -> W.Problem:
-    kw.setdefault("dtype", W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16)
+    kw.setdefault("dtype", {"f32": W.WKV_F32, "bf16": W.WKV_BF16, "f16": W.WKV_F16}[w.dtype])
     return W.Problem(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, w_obs=w.w_obs,
                      seq_len=w.seq_len, win=w.win, top_p=w.top_p, k_windows=w.k_windows,
                      max_seq_len=w.max_seq_len, **kw)

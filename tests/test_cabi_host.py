@@ -187,3 +187,18 @@ def test_header_is_c99_and_library_links_from_c(tmp_path):
     d = W.wkv_get_dims(_problem())
     assert out[:5] == ["0", str(d.obs_rows), str(d.nw_max), str(d.k_max), str(d.nkeep_max)]
     assert int(out[5]) == W.wkv_workspace_bytes(_problem(), 1) and out[6] == "ok"
+
+
+def test_host_side_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The validation / sizing / planning code of the library, built for the CPU with ASan + UBSan and
+    driven through every entry point with valid and invalid arguments (tests/c/cabi_validation.cpp;
+    the kernel launchers are replaced by stand-ins, so no GPU is involved)."""
+    import subprocess
+    from paper_2503_17922_amd import build as B
+    exe = B.build_host_sanitized(str(tmp_path), [os.path.join(ROOT, "tests", "c", "cabi_validation.cpp"),
+                                                 os.path.join(ROOT, "tests", "c", "launch_stubs.cpp")])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)          # the sanitizer runtime must come first in the link order of the process
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
+    assert res.stdout.strip().endswith("ok (0 checks failed)")

@@ -40,7 +40,7 @@ def _decode_and_check(w, device, n_steps, extra_rows, as_f16=False):
     layer, g = 0, 0
     n_valid = st.n_keep[g].clone()                                   # [B, H]
     shape = W.DecodeShape(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, capacity=cap,
-                          dtype=W.WKV_F16 if as_f16 else (W.WKV_F32 if w.dtype == "f32" else W.WKV_BF16))
+                          dtype=W.WKV_F16 if as_f16 else {"f32": W.WKV_F32, "bf16": W.WKV_BF16, "f16": W.WKV_F16}[w.dtype])
     ws = torch.empty(W.wkv_decode_workspace_bytes(shape), dtype=torch.uint8, device=device)
     out = torch.full((B, Hq, d), -5.0, dtype=torch.float32, device=device)
     # oracle state: the retained rows of every (b, h), widened exactly
@@ -111,6 +111,64 @@ def test_decode_fp16(device, kw):
                 w_obs=16, seq_len=[900, 300], win=[8, 16], top_p=[8, 8], k_windows=[30, 6])
     base.update(kw)
     _decode_and_check(S.Workload(**base), device, n_steps=3, extra_rows=8, as_f16=True)
+
+
+def test_decode_half_values(device):
+    # IEEE half tensors drawn as half (11 significant bits: values bf16 cannot hold)
+    w = S.Workload(name="dec_half", seed=96, dtype="f16", n_groups=1, gamma=1, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                   w_obs=16, seq_len=[900, 300], win=[8, 16], top_p=[8, 8], k_windows=[30, 6])
+    st, *_ = _decode_and_check(w, device, n_steps=3, extra_rows=8)
+    assert not torch.equal(st.k[0].to(torch.bfloat16).to(torch.float16), st.k[0]), "the inputs fit bf16: not a test of half"
+
+
+def test_decode_all_layers_of_a_group_share_one_counter(device):
+    # Section 2.2.2: the gamma layers of a group share one index set, hence one row count per
+    # (sequence, KV head).  The n_keep row of the compression call itself serves as that counter:
+    # the first gamma-1 layers run with WKV_DECODE_KEEP_COUNT, the last one advances it.
+    w = S.Workload(name="dec_group", seed=97, dtype="bf16", n_groups=2, gamma=3, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                   w_obs=16, seq_len=[1200, 500], win=[8, 16], top_p=[8, 6], k_windows=[40, 9])
+    B, H, Hq, d, G = w.batch, w.n_kv_heads, w.n_q_heads, w.head_dim, w.q_per_kv
+    nk = W.wkv_get_dims(P.make_problem(w)).nkeep_max
+    cap = nk + 4
+    st = P.DeviceState(w, device)
+    st.problem = P.make_problem(w, out_strides=(H * cap * d, cap * d, d))
+    st.k_out = [torch.full((B, H, cap, d), 7.0, dtype=torch.bfloat16, device=device) for _ in range(w.n_layers)]
+    st.v_out = [torch.full((B, H, cap, d), 7.0, dtype=torch.bfloat16, device=device) for _ in range(w.n_layers)]
+    st.compress()
+    keep = W.DecodeShape(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, capacity=cap, dtype=W.WKV_BF16,
+                         flags=W.WKV_DECODE_KEEP_COUNT)
+    bump = W.DecodeShape(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, capacity=cap, dtype=W.WKV_BF16)
+    ws = torch.empty(W.wkv_decode_workspace_bytes(bump), dtype=torch.uint8, device=device)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device=device)
+    g = 1
+    n0 = st.n_keep[g].cpu().numpy().copy()
+    ok = {(l, b, h): P.host_f64(w, st.k_out[g * w.gamma + l][b, h, : n0[b, h]]) for l in range(w.gamma) for b in range(B) for h in range(H)}
+    ov = {(l, b, h): P.host_f64(w, st.v_out[g * w.gamma + l][b, h, : n0[b, h]]) for l in range(w.gamma) for b in range(B) for h in range(H)}
+    for step in range(2):
+        for l in range(w.gamma):
+            layer = g * w.gamma + l
+            q = _new_token(w, device, 10 * step + l, 0, (B, Hq, d))
+            kn = _new_token(w, device, 10 * step + l, 1, (B, H, d)); vn = _new_token(w, device, 10 * step + l, 2, (B, H, d))
+            W.wkv_decode_step(keep if l < w.gamma - 1 else bump, q, kn, vn, st.k_out[layer], st.v_out[layer], st.n_keep[g], out, ws)
+            torch.cuda.synchronize()
+            want_count = n0 + step + (1 if l == w.gamma - 1 else 0)
+            assert np.array_equal(st.n_keep[g].cpu().numpy(), want_count), f"step {step} layer {l}: counter"
+            for b, h in itertools.product(range(B), range(H)):
+                want, ok[l, b, h], ov[l, b, h] = O.decode_step(P.host_f64(w, q[b, h * G:(h + 1) * G]), ok[l, b, h], ov[l, b, h],
+                                                               P.host_f64(w, kn[b, h]), P.host_f64(w, vn[b, h]))
+                np.testing.assert_allclose(out[b, h * G:(h + 1) * G].cpu().numpy(), want, rtol=RTOL, atol=ATOL,
+                                           err_msg=f"step {step} layer {l} b{b} h{h}")
+                n = ok[l, b, h].shape[0]
+                assert np.array_equal(P.host_f64(w, st.k_out[layer][b, h, :n]), ok[l, b, h])
+                assert np.array_equal(P.host_f64(w, st.v_out[layer][b, h, :n]), ov[l, b, h])
+    assert np.array_equal(st.n_keep[0].cpu().numpy(), _fresh_n_keep(st, 0))
+
+
+def _fresh_n_keep(st, g):
+    """The other group's counters are what a fresh compression gives (nothing touched them)."""
+    ref = P.DeviceState(st.w, st.device)
+    ref.compress()
+    return ref.n_keep[g].cpu().numpy()
 
 
 def test_decode_full_cache_is_refused_per_row(device):

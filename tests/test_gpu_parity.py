@@ -23,40 +23,64 @@ def _sample(items, n, seed):
     return [items[i] for i in sorted(pick)]
 
 
-def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check_stage_group=0, as_f16=False):
+def batched_intermediates(st):
+    """What the batched call left in its workspace: (t or None, s or None) as float64 host arrays
+    [G, B, H, t_stride] / [G, B, H, nw_max] (the library says which of the two it writes)."""
+    w, d = st.w, st.dims
+    lay = W.wkv_get_workspace_layout(st.problem, w.n_groups)
+    assert lay.t_written + lay.s_written == 1
+    rows = w.n_groups * w.batch * w.n_kv_heads
+
+    def view(offset, cols):
+        n = rows * max(cols, 1)
+        x = st.workspace[offset: offset + 4 * n].view(torch.float32).view(w.n_groups, w.batch, w.n_kv_heads, max(cols, 1))
+        with np.errstate(invalid="ignore"):          # entries past a row's end are whatever the workspace held
+            return x.cpu().numpy().astype(np.float64)
+    return (view(lay.t_offset, d.t_stride) if lay.t_written else None,
+            view(lay.s_offset, d.nw_max) if lay.s_written else None)
+
+
+def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, stage_groups=None, as_f16=False):
     """One wkv_compress_groups call checked against the oracle.
 
     n_oracle: how many (group, b, h) problems the oracle recomputes (None = all).
     n_gather_cpu: how many (layer, K|V, b, h) slices are compared on the CPU with the oracle's
     gather (None = all); every slice is additionally compared on the device.
+    stage_groups: the groups whose four stage calls are run and compared too (None = all).
+    For every oracle problem the token scores t and window scores s of the stage calls AND what the
+    batched call itself computed (its s, or its t when it pools in the selection kernel, read back
+    from the workspace) are compared element by element.
     """
     st = P.DeviceState(w, device, as_f16=as_f16)
     print(f"[{w.name}] L={w.seq_len} win={w.win} p={w.top_p} k={w.k_windows} groups={w.n_groups}x{w.gamma} "
           f"ws={st.ws_bytes >> 10} KiB", flush=True)
-    if not as_f16:
+    if not as_f16 and w.dtype != "f16":
         P.check_generator_matches(w, S.KIND_K, 0, st.k[0], 0, 0)
         P.check_generator_matches(w, S.KIND_V, w.n_layers - 1, st.v[-1], w.batch - 1, w.n_kv_heads - 1)
     k_before = st.k[0][0, 0, : min(64, w.seq_len[0])].clone()
     st.compress()
     assert torch.equal(k_before, st.k[0][0, 0, : min(64, w.seq_len[0])]), "inputs were modified"
+    t_fused, s_fused = batched_intermediates(st)
 
     win_idx = st.win_idx.cpu().numpy()[..., : st.dims.k_max]          # (allocated with >= 1 column)
     tok_idx = st.tok_idx.cpu().numpy(); n_keep = st.n_keep.cpu().numpy()
     B, H = w.batch, w.n_kv_heads
 
     # ---- stage calls reproduce the batched call bit for bit, and expose t and s ----------------
-    g0 = check_stage_group
-    t_dev, s_dev, wi, ti, nk = st.stages(g0)
-    assert np.array_equal(wi.cpu().numpy()[..., : st.dims.k_max], win_idx[g0]) and np.array_equal(ti.cpu().numpy(), tok_idx[g0])
-    assert np.array_equal(nk.cpu().numpy(), n_keep[g0])
-    # the gather stage, one layer at a time (as prefill would produce them), equals the batched gather
-    for l in range(g0 * w.gamma, (g0 + 1) * w.gamma):
-        ko = torch.full_like(st.k_out[l], 9.0); vo = torch.full_like(st.v_out[l], 9.0)
-        W.wkv_gather_group(st.problem, [st.k[l]], [st.v[l]], ti, nk, [ko], [vo])
-        torch.cuda.synchronize()
-        assert torch.equal(ko, st.k_out[l]) and torch.equal(vo, st.v_out[l]), f"{w.name}: stage gather of layer {l}"
-    t_host = t_dev.cpu().numpy().astype(np.float64)[..., : st.dims.t_stride]
-    s_host = s_dev.cpu().numpy().astype(np.float64)[..., : st.dims.nw_max]
+    stage_groups = list(range(w.n_groups)) if stage_groups is None else list(stage_groups)
+    t_stage, s_stage = {}, {}
+    for g0 in stage_groups:
+        t_dev, s_dev, wi, ti, nk = st.stages(g0)
+        assert np.array_equal(wi.cpu().numpy()[..., : st.dims.k_max], win_idx[g0]) and np.array_equal(ti.cpu().numpy(), tok_idx[g0])
+        assert np.array_equal(nk.cpu().numpy(), n_keep[g0])
+        # the gather stage, one layer at a time (as prefill would produce them), equals the batched gather
+        for l in range(g0 * w.gamma, (g0 + 1) * w.gamma):
+            ko = torch.full_like(st.k_out[l], 9.0); vo = torch.full_like(st.v_out[l], 9.0)
+            W.wkv_gather_group(st.problem, [st.k[l]], [st.v[l]], ti, nk, [ko], [vo])
+            torch.cuda.synchronize()
+            assert torch.equal(ko, st.k_out[l]) and torch.equal(vo, st.v_out[l]), f"{w.name}: stage gather of layer {l}"
+        t_stage[g0] = t_dev.cpu().numpy().astype(np.float64)[..., : st.dims.t_stride]
+        s_stage[g0] = s_dev.cpu().numpy().astype(np.float64)[..., : st.dims.nw_max]
 
     # ---- structure of every index row -------------------------------------------------------------
     sels = {}
@@ -66,23 +90,25 @@ def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, check
 
     # ---- oracle on (sampled) problems ----------------------------------------------------------------
     problems = _sample(itertools.product(range(w.n_groups), range(B), range(H)), n_oracle, 1)
-    if (g0, 0, 0) not in problems:
-        problems.append((g0, 0, 0))
     exact = 0
     for g, b, h in problems:
         t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
         what = f"{w.name} g{g} b{b} h{h}"
-        if g == g0:
-            n_rev = w.seq_len[b] - w.w_obs
-            P.assert_scores_close(t_host[b, h, :n_rev], t, what + " t")
-            assert np.all(t_host[b, h, n_rev:] == 0.0), what + " t padding"
-            P.assert_scores_close(s_host[b, h, : len(s)], s, what + " s")
-            assert np.all(np.isneginf(s_host[b, h, len(s):])), what + " s padding"
+        n_rev = w.seq_len[b] - w.w_obs
+        if g in t_stage:
+            P.assert_scores_close(t_stage[g][b, h, :n_rev], t, what + " t (stage call)")
+            assert np.all(t_stage[g][b, h, n_rev:] == 0.0), what + " t padding"
+            P.assert_scores_close(s_stage[g][b, h, : len(s)], s, what + " s (stage call)")
+            assert np.all(np.isneginf(s_stage[g][b, h, len(s):])), what + " s padding"
+        if s_fused is not None:
+            P.assert_scores_close(s_fused[g, b, h, : len(s)], s, what + " s (batched call)")
+        if t_fused is not None and n_rev > 0:
+            P.assert_scores_close(t_fused[g, b, h, :n_rev], t, what + " t (batched call)")
         same = P.check_selection(s, sel, sels[g, b, h], w.k_windows[b], what)
         exact += same
         if same:
             assert np.array_equal(tok_idx[g, b, h, : len(idx)], idx), what + " tok_idx"
-    print(f"[{w.name}] oracle problems: {len(problems)}, identical selections: {exact}", flush=True)
+    print(f"[{w.name}] oracle problems: {len(problems)} of {w.n_groups * B * H}, identical selections: {exact}", flush=True)
 
     # ---- gather: every layer, bit exact ----------------------------------------------------------------
     slices = list(itertools.product(range(w.n_layers), (S.KIND_K, S.KIND_V), range(B), range(H)))
@@ -120,7 +146,7 @@ def test_config_small(name, device):
 
 def test_config_c4_full_model(device):
     w = S.make_workload("c4")
-    st, sels = run_and_check(w, device, n_oracle=24, n_gather_cpu=12, check_stage_group=3)
+    st, sels = run_and_check(w, device, n_gather_cpu=12)          # the oracle on all 64 (group, KV head) problems
     # every window inside a planted span is kept, in every KV head of every scoring layer
     for (g, b, h), sel in sels.items():
         kept = set(int(x) for x in sel)
@@ -133,12 +159,12 @@ def test_config_c4_eight_query_heads_per_kv_head(device):
     # the 32K configuration with 64 query heads on 8 KV heads (70B-class): 256 softmax rows per KV
     # head, the two-half workgroups at their full chunk plan (3 groups of 2 layers keep it light)
     w = S.scaled_workload(S.make_workload("c4"), name="c4g8", n_q_heads=64, n_groups=3, gamma=2)
-    run_and_check(w, device, n_oracle=6, n_gather_cpu=8, check_stage_group=1)
+    run_and_check(w, device, n_gather_cpu=8)
 
 
 def test_config_c5_batched_mixed(device):
     w = S.make_workload("c5")
-    run_and_check(w, device, n_oracle=32, n_gather_cpu=16, check_stage_group=5)
+    run_and_check(w, device, n_gather_cpu=16)                     # the oracle on all 512 (group, sequence, KV head) problems
 
 
 def test_longest_supported_window_count(device):
@@ -147,7 +173,7 @@ def test_longest_supported_window_count(device):
     w = S.Workload(name="long", seed=1006, dtype="bf16", n_groups=1, gamma=1, n_q_heads=32, n_kv_heads=8, head_dim=128,
                    w_obs=32, seq_len=[8 * 32768 + 32], win=[8], top_p=[8], k_windows=[3000])
     assert W.wkv_get_dims(P.make_problem(w)).nw_max == W.WKV_MAX_WINDOWS
-    run_and_check(w, device, n_oracle=2, n_gather_cpu=4)
+    run_and_check(w, device, n_gather_cpu=4)
     with pytest.raises(W.WkvError) as e:                 # one window more is refused on the host
         W.wkv_get_dims(P.make_problem(S.scaled_workload(w, seq_len=[8 * 32768 + 33])))
     assert e.value.status == W.WKV_ERR_UNSUPPORTED
@@ -246,6 +272,42 @@ def test_fp16_inputs(kw, device):
 
 def test_fp16_config_c2(device):
     run_and_check(S.make_workload("c2"), device, as_f16=True)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                                               # 128 rows, ragged tail
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[2500, 900], win=[16, 8], top_p=[8, 8], k_windows=[20, 11]),   # 256 rows
+    dict(head_dim=64, seq_len=[3000], win=[24], top_p=[7], k_windows=[40]),     # pooling in the selection kernel
+])
+def test_half_inputs_with_half_values(kw, device):
+    # IEEE half tensors drawn as half: 11 significant bits, so the _f16 MFMA operands carry mantissa
+    # bits that bf16-valued inputs never set
+    w = _mini(dtype="f16", **kw)
+    st, _ = run_and_check(w, device)
+    assert not torch.equal(st.k[0].to(torch.bfloat16).to(torch.float16), st.k[0]), "the inputs fit bf16: not a test of half"
+
+
+def test_half_values_config_c2_shape(device):
+    run_and_check(S.scaled_workload(S.make_workload("c2"), name="c2h", dtype="f16"), device)
+
+
+def test_single_group_entry_point(device):
+    # wkv_compress_group (one group, the call Section 2.2 describes) gives what the batched call gives
+    w = _mini(seq_len=[1500, 700], win=[8, 16], top_p=[8, 5], k_windows=[40, 9], n_groups=1, gamma=3)
+    ref = P.DeviceState(w, device); ref.compress()
+    st = P.DeviceState(w, device)
+    W.wkv_compress_group(st.problem, w.gamma, st.q[0], None, st.k, st.v, st.k_out, st.v_out, st.win_idx[0], st.tok_idx[0],
+                         st.n_keep[0], st.workspace)
+    torch.cuda.synchronize()
+    for a, b in zip((st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out),
+                    (ref.win_idx, ref.tok_idx, ref.n_keep, *ref.k_out, *ref.v_out)):
+        assert torch.equal(a, b)
+    lse = st.oracle_lse(0)                      # and with the normalisers handed over
+    ref.compress(lse=[lse])
+    W.wkv_compress_group(st.problem, w.gamma, st.q[0], lse, st.k, st.v, st.k_out, st.v_out, st.win_idx[0], st.tok_idx[0],
+                         st.n_keep[0], st.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(st.tok_idx, ref.tok_idx) and torch.equal(st.k_out[2], ref.k_out[2])
 
 
 def test_large_logits_are_stable(device):
@@ -373,12 +435,14 @@ def test_lse_handoff_full_model(device):
     lse = [st.oracle_lse(g) for g in range(w.n_groups)]
     st.compress(lse=lse)
     win = st.win_idx.cpu().numpy(); tok = st.tok_idx.cpu().numpy(); nkeep = st.n_keep.cpu().numpy()
-    problems = _sample(itertools.product(range(w.n_groups), range(w.batch), range(w.n_kv_heads)), 12, 3)
-    for g, b, h in itertools.product(range(w.n_groups), range(w.batch), range(w.n_kv_heads)):
+    problems = list(itertools.product(range(w.n_groups), range(w.batch), range(w.n_kv_heads)))      # all 64
+    for g, b, h in problems:
         P.check_indices_structure(w, b, win[g, b, h], tok[g, b, h], int(nkeep[g, b, h]), st.dims.k_max, st.dims.nkeep_max,
                                   f"c4 lse g{g} b{b} h{h}")
+    _, s_fused = batched_intermediates(st)
     for g, b, h in problems:
         t, s, sel, idx = P.oracle_problem(w, st.q[g], st.k[g * w.gamma], b, h)
+        P.assert_scores_close(s_fused[g, b, h, : len(s)], s, f"c4 lse g{g} b{b} h{h} s (batched call)")
         if P.check_selection(s, sel, win[g, b, h, : w.k_windows[b]], w.k_windows[b], f"c4 lse g{g} b{b} h{h}"):
             assert np.array_equal(tok[g, b, h, : len(idx)], idx)
         rows = torch.from_numpy(tok[g, b, h, : nkeep[g, b, h]].astype(np.int64)).to(device)

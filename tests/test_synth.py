@@ -12,7 +12,7 @@ def _bits(t):
     return t.contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_numpy_and_torch_generators_agree(dtype):
     st = S.stream_id(S.KIND_K, 5)
     a = S.normal_np(42, st, 123, 70000, dtype)
@@ -34,6 +34,22 @@ def test_bf16_rounding_is_nearest_even():
     want = _bits(torch.from_numpy(x).to(torch.bfloat16))
     assert np.array_equal(got, want)
     assert np.array_equal(S.bf16_bits_to_f64(got), torch.from_numpy(x).to(torch.bfloat16).double().numpy())
+
+
+def test_half_stream_rounds_to_nearest_and_uses_halfs_mantissa():
+    x = S.normal_table_f32()
+    bits = S.normal_table_f16_bits()
+    assert np.array_equal(bits, _bits(torch.from_numpy(x.copy()).to(torch.float16)))
+    wide = S.f16_bits_to_f64(bits)
+    assert np.array_equal(wide, torch.from_numpy(x.copy()).to(torch.float16).double().numpy())
+    assert np.abs(wide - x).max() <= 2.0 ** -10 * np.abs(x).max()
+    # most entries are NOT representable in bf16: the stream carries more than 8 significant bits
+    assert (S.bf16_bits_to_f64(S.f32_to_bf16_bits(wide.astype(np.float32))) != wide).mean() > 0.8
+    w = S.Workload(name="h", seed=3, dtype="f16", n_groups=1, gamma=1, n_q_heads=2, n_kv_heads=1, head_dim=64, w_obs=4,
+                   seq_len=[50], win=[8], top_p=[8], k_windows=[1], outlier_channels=2)
+    full = _bits(w.kv_torch(S.KIND_K, 0, "cpu"))
+    assert np.array_equal(full[0, 0], w.kv_np(S.KIND_K, 0, 0, 0))
+    assert np.array_equal(w.to_f64(w.kv_np(S.KIND_K, 0, 0, 0)), w.kv_torch(S.KIND_K, 0, "cpu")[0, 0].double().numpy())
 
 
 def test_workload_table():

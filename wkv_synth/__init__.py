@@ -96,6 +96,23 @@ def normal_table_bf16_bits() -> np.ndarray:
     return f32_to_bf16_bits(normal_table_f32())
 
 
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to IEEE half (round to nearest even); returns the uint16 bit patterns."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f64(b: np.ndarray) -> np.ndarray:
+    """Widen IEEE half bit patterns (uint16) exactly to float64."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+@lru_cache(maxsize=None)
+def normal_table_f16_bits() -> np.ndarray:
+    """The float32 table rounded to IEEE half: 11 significant bits, so products and sums of these
+    values exercise half's mantissa (unlike bf16-valued numbers stored as half)."""
+    return f32_to_f16_bits(normal_table_f32())
+
+
 def table_index_np(seed: int, stream: int, start: int, count: int) -> np.ndarray:
     """Table indices (0..65535) of elements ``start .. start+count-1`` of a stream."""
     base = stream_base(seed, stream)
@@ -104,12 +121,14 @@ def table_index_np(seed: int, stream: int, start: int, count: int) -> np.ndarray
 
 
 def normal_np(seed: int, stream: int, start: int, count: int, dtype: str) -> np.ndarray:
-    """Host slice of a stream. ``dtype`` 'f32' -> float32 values, 'bf16' -> uint16 bits."""
+    """Host slice of a stream. ``dtype`` 'f32' -> float32 values, 'bf16' / 'f16' -> uint16 bits."""
     idx = table_index_np(seed, stream, start, count)
     if dtype == "f32":
         return normal_table_f32()[idx]
     if dtype == "bf16":
         return normal_table_bf16_bits()[idx]
+    if dtype == "f16":
+        return normal_table_f16_bits()[idx]
     raise ValueError(dtype)
 
 
@@ -148,6 +167,10 @@ def normal_torch(seed: int, stream: int, numel: int, dtype: str, device, start: 
         bits = normal_table_bf16_bits().view(np.int16).copy()
         table = torch.from_numpy(bits).to(device).view(torch.bfloat16)
         out = torch.empty(numel, dtype=torch.bfloat16, device=device)
+    elif dtype == "f16":
+        bits = normal_table_f16_bits().view(np.int16).copy()
+        table = torch.from_numpy(bits).to(device).view(torch.float16)
+        out = torch.empty(numel, dtype=torch.float16, device=device)
     else:
         raise ValueError(dtype)
     for lo in range(0, numel, chunk):
@@ -182,7 +205,7 @@ class Workload:
 
     name: str
     seed: int
-    dtype: str                      # 'f32' | 'bf16'
+    dtype: str                      # 'f32' | 'bf16' | 'f16'
     n_groups: int
     gamma: int                      # layers per group
     n_q_heads: int
@@ -305,9 +328,12 @@ class Workload:
         x = x.copy()
         if self.dtype == "f32":
             x[:, ch] *= np.float32(8.0)
-        else:  # widening, scaling by a power of two and narrowing again are all exact
+        elif self.dtype == "bf16":  # widening, scaling by a power of two and narrowing again are all exact
             v = bf16_bits_to_f64(x[:, ch]) * 8.0
             x[:, ch] = f32_to_bf16_bits(v.astype(np.float32))
+        else:                       # half: |value| * 8 < 64, far inside its range, so exact as well
+            v = f16_bits_to_f64(x[:, ch]) * 8.0
+            x[:, ch] = f32_to_f16_bits(v.astype(np.float32))
         return x
 
     def span_rows_np(self, group: int, b: int, h: int) -> np.ndarray:
@@ -324,7 +350,7 @@ class Workload:
             return self._cache[key]
         d, G = self.head_dim, self.q_per_kv
         q = self.q_obs_np(group)[b, h * G:(h + 1) * G]
-        qf = bf16_bits_to_f64(q) if self.dtype == "bf16" else q.astype(np.float64)
+        qf = self.to_f64(q)
         qhat = qf.reshape(-1, d).mean(0)
         qhat /= np.linalg.norm(qhat)
         n = self.planted_spans * self.span_len
@@ -335,7 +361,7 @@ class Workload:
         c = self.span_cos
         rows = math.sqrt(d) * (c * qhat[None, :] + math.sqrt(1.0 - c * c) * u)
         rows = rows.astype(np.float32)
-        out = rows if self.dtype == "f32" else f32_to_bf16_bits(rows)
+        out = rows if self.dtype == "f32" else (f32_to_bf16_bits(rows) if self.dtype == "bf16" else f32_to_f16_bits(rows))
         self._cache[key] = out
         return out
 
@@ -352,13 +378,13 @@ class Workload:
     # ---- device tensors (what the GPU path is fed) -------------------------------------
     def _torch_dtype(self):
         import torch
-        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+        return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.dtype]
 
     def _np_to_torch(self, x: np.ndarray, device):
         import torch
         if self.dtype == "f32":
             return torch.from_numpy(np.ascontiguousarray(x)).to(device)
-        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(device).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(device).view(self._torch_dtype())
 
     def q_obs_torch(self, group: int, device):
         n = int(np.prod(self.q_shape()))
@@ -385,7 +411,9 @@ class Workload:
     # ---- conversions ---------------------------------------------------------------------
     def to_f64(self, x: np.ndarray) -> np.ndarray:
         """Widen a host slice in the workload dtype exactly to float64."""
-        return bf16_bits_to_f64(x) if self.dtype == "bf16" else x.astype(np.float64)
+        if self.dtype == "bf16":
+            return bf16_bits_to_f64(x)
+        return f16_bits_to_f64(x) if self.dtype == "f16" else x.astype(np.float64)
 
 
 def _llama(name, seed, seq_len, win, top_p, k, n_groups, **kw) -> Workload:
