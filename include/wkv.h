@@ -341,6 +341,26 @@ wkv_status wkv_decode_step(const wkv_decode_shape *shape, const void *q_new, con
                            const void *v_new, void *k_cache, void *v_cache, int32_t *n_valid,
                            float *out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * wkv_decode_step for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the
+ * workspace), same kernels, same results; the partial results of the key ranges go to a scratch
+ * array that is part of the library's device image (WKV_DECODE_STATIC_SCRATCH_BYTES, held by every
+ * GPU the library runs on until the process ends) instead of caller memory.  The call allocates
+ * and frees nothing.
+ *   - A shape whose wkv_decode_workspace_bytes exceeds WKV_DECODE_STATIC_SCRATCH_BYTES is refused
+ *     with WKV_ERR_WORKSPACE before anything is launched (use wkv_decode_step with a workspace).
+ *   - All calls on one GPU share that GPU's scratch array: calls that may overlap in time on one
+ *     GPU (different streams, different threads) race on it and must be serialised by the caller.
+ *     Nothing in it needs to survive from one call to the next.
+ *   - The first call on a device looks up the array's address (no stream work, no allocation);
+ *     make that first call outside graph capture.
+ */
+#define WKV_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+wkv_status wkv_decode_step_static(const wkv_decode_shape *shape, const void *q_new, const void *k_new,
+                                  const void *v_new, void *k_cache, void *v_cache, int32_t *n_valid,
+                                  float *out, void *hip_stream);
+
 const char *wkv_status_string(wkv_status status);
 
 /* Message describing the most recent failure on the calling thread ("" if none). */

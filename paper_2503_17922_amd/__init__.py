@@ -26,7 +26,8 @@ STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_get_workspace_layout", "wkv_score", "wkv_window_pool",
            "wkv_topk_windows", "wkv_gather_group", "wkv_compress_group", "wkv_compress_groups",
            "wkv_compress_groups_profiled", "wkv_group_budgets", "wkv_status_string", "wkv_last_error",
-           "wkv_decode_workspace_bytes", "wkv_decode_step", "wkv_index_jaccard")
+           "wkv_decode_workspace_bytes", "wkv_decode_step", "wkv_decode_step_static", "wkv_index_jaccard")
+WKV_DECODE_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class WkvError(RuntimeError):
@@ -103,6 +104,7 @@ def lib() -> C.CDLL:
     DP = C.POINTER(_DecodeShape)
     l.wkv_decode_workspace_bytes.argtypes = [DP]; l.wkv_decode_workspace_bytes.restype = C.c_size_t
     l.wkv_decode_step.argtypes = [DP, VP, VP, VP, VP, VP, VP, VP, VP, C.c_size_t, VP]; l.wkv_decode_step.restype = C.c_int
+    l.wkv_decode_step_static.argtypes = [DP, VP, VP, VP, VP, VP, VP, VP, VP]; l.wkv_decode_step_static.restype = C.c_int
     l.wkv_status_string.argtypes = [C.c_int]; l.wkv_status_string.restype = C.c_char_p
     l.wkv_last_error.argtypes = []; l.wkv_last_error.restype = C.c_char_p
     _lib = l
@@ -287,6 +289,11 @@ def wkv_decode_step(shape: DecodeShape, q_new, k_new, v_new, k_cache, v_cache, n
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().wkv_decode_step(shape.ref(), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                  _ptr(n_valid), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def wkv_decode_step_static(shape: DecodeShape, q_new, k_new, v_new, k_cache, v_cache, n_valid, out, stream=None) -> None:
+    _check(lib().wkv_decode_step_static(shape.ref(), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                        _ptr(n_valid), _ptr(out), _stream(stream)))
 
 
 def wkv_group_budgets(b_total: float, n_groups: int, lam: float) -> List[float]:

@@ -294,4 +294,26 @@ wkv_status wkv_decode_step(const wkv_decode_shape *shape, const void *q_new, con
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_decode_step launch");
 }
 
+wkv_status wkv_decode_step_static(const wkv_decode_shape *shape, const void *q_new, const void *k_new,
+                                  const void *v_new, void *k_cache, void *v_cache, int32_t *n_valid, float *out,
+                                  void *hip_stream) {
+  Decode dc;
+  wkv_status st = validate_decode(shape, &dc);
+  if (st != WKV_OK) return st;
+  if (!q_new || !k_new || !v_new || !k_cache || !v_cache || !n_valid || !out) {
+    set_error("q_new / k_new / v_new / k_cache / v_cache / n_valid / out is NULL"); return WKV_ERR_INVALID_ARG;
+  }
+  if (misaligned(q_new, 16) || misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(k_cache, 16) ||
+      misaligned(v_cache, 16)) {
+    set_error("q_new, k_new, v_new and the caches must be 16-byte aligned"); return WKV_ERR_INVALID_ARG;
+  }
+  if (dc.ws_bytes > WKV_DECODE_STATIC_SCRATCH_BYTES) {
+    set_error("this shape needs %zu bytes of scratch, the static array holds %u: use wkv_decode_step with a workspace",
+              dc.ws_bytes, (unsigned)WKV_DECODE_STATIC_SCRATCH_BYTES);
+    return WKV_ERR_WORKSPACE;
+  }
+  hipError_t e = launch_decode_static(dc.shape, q_new, k_new, v_new, k_cache, v_cache, n_valid, out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_decode_step_static launch");
+}
+
 }  // extern "C"

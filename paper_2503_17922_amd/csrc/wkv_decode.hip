@@ -17,9 +17,17 @@
 //                   once at the end and the workgroup writes (m, l, o) to the workspace.
 //   combine kernel  grid (B*Hkv): merges the splits, normalises, writes fp32 output, bumps the
 //                   row count.
+#include <atomic>
+#include <mutex>
+
 #include "wkv_device.h"
 
 namespace wkv {
+
+// Scratch memory of wkv_decode_step_static: part of the device image, one copy per GPU at that
+// GPU's own address.  In host code the name is only a handle for hipGetSymbolAddress; the device
+// address found there (per device, once) is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[WKV_DECODE_STATIC_SCRATCH_BYTES];
 
 constexpr int DEC_THREADS = 256;
 constexpr int DEC_WAVES = DEC_THREADS / 64;
@@ -497,6 +505,32 @@ hipError_t launch_decode(const DecodeShape &s, const void *q_new, const void *k_
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(decode_combine_kernel, dim3(s.B * s.Hkv), dim3(DEC_THREADS), 0, stream, s, part, n_valid, out);
   return hipGetLastError();
+}
+
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void *> scratch_ptr[MAX_DEVICES];
+static std::mutex scratch_mutex;
+
+hipError_t launch_decode_static(const DecodeShape &s, const void *q_new, const void *k_new, const void *v_new,
+                                void *k_cache, void *v_cache, int32_t *n_valid, float *out, hipStream_t stream) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {                                 // first call on this device (which is the current one)
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    p = scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!p) return hipErrorInvalidSymbol;
+      scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  // every partial result a combine reads is written by the partial kernel of the same call:
+  // nothing in the array has to be cleared
+  return launch_decode(s, q_new, k_new, v_new, k_cache, v_cache, n_valid, out, (float *)p, stream);
 }
 
 }  // namespace wkv

@@ -125,4 +125,9 @@ wkv_status validate_decode(const wkv_decode_shape *p, Decode *out);
 hipError_t launch_decode(const DecodeShape &s, const void *q_new, const void *k_new, const void *v_new, void *k_cache,
                          void *v_cache, int32_t *n_valid, float *out, float *part, hipStream_t stream);
 
+// The same launches with the partial results in the library's own static scratch array of the
+// current device (no workspace argument; the caller has checked that the shape fits).
+hipError_t launch_decode_static(const DecodeShape &s, const void *q_new, const void *k_new, const void *v_new,
+                                void *k_cache, void *v_cache, int32_t *n_valid, float *out, hipStream_t stream);
+
 }  // namespace wkv

@@ -112,6 +112,15 @@ int main() {
   ds.flags = 0;
   EXPECT(wkv_decode_step(&ds, dev, dev, dev, dev, dev, idev, fdev, dev, dws - 1, nullptr) == WKV_ERR_WORKSPACE);
   EXPECT(wkv_decode_step(&ds, dev, dev, dev, dev, dev, nullptr, fdev, dev, dws, nullptr) == WKV_ERR_INVALID_ARG);
+  before = wkv_stub_launches;
+  EXPECT(wkv_decode_step_static(&ds, dev, dev, dev, dev, dev, idev, fdev, nullptr) == WKV_OK);
+  EXPECT(wkv_stub_launches == before + 1);
+  EXPECT(wkv_decode_step_static(&ds, dev, dev, nullptr, dev, dev, idev, fdev, nullptr) == WKV_ERR_INVALID_ARG);
+  ds.batch = 4000;                    // 32000 rows of partial results: beyond the static scratch array
+  EXPECT(wkv_decode_workspace_bytes(&ds) > WKV_DECODE_STATIC_SCRATCH_BYTES);
+  EXPECT(wkv_decode_step_static(&ds, dev, dev, dev, dev, dev, idev, fdev, nullptr) == WKV_ERR_WORKSPACE);
+  EXPECT(wkv_stub_launches == before + 1);
+  ds.batch = 64;
   ds.n_q_heads = 72;
   EXPECT(wkv_decode_workspace_bytes(&ds) == 0);
   // ---- budgets (Eq. 5-7) ----------------------------------------------------------------------------------------

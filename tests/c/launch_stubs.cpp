@@ -19,4 +19,6 @@ hipError_t launch_gather(const Shape &, const LayerPtrs &, int32_t, int32_t, con
 hipError_t launch_jaccard(const Shape &, int32_t, const int32_t *, const int32_t *, float *, hipStream_t) { ++wkv_stub_launches; return hipSuccess; }
 hipError_t launch_decode(const DecodeShape &, const void *, const void *, const void *, void *, void *, int32_t *, float *,
                          float *, hipStream_t) { ++wkv_stub_launches; return hipSuccess; }
+hipError_t launch_decode_static(const DecodeShape &, const void *, const void *, const void *, void *, void *, int32_t *,
+                                float *, hipStream_t) { ++wkv_stub_launches; return hipSuccess; }
 }  // namespace wkv
