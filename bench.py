@@ -227,6 +227,8 @@ def main():
     ap.add_argument("--keep-padding", action="store_true",
                     help="set WKV_KEEP_PADDING: compact-cache rows past n_keep are not zero-filled (matters for "
                          "batches of mixed lengths; the default run zero-fills)")
+    ap.add_argument("--score", choices=["auto", "two-pass", "single-read"], default="auto",
+                    help="which kernels compute Eq. 1-2: the library's choice (default), or one of the two forced")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for hardware counters)")
     args = ap.parse_args()
@@ -244,7 +246,9 @@ def main():
     W.lib()
     device = torch.device("cuda:0")
     w = S.make_workload(args.workload)
-    st = P.DeviceState(w, device, flags=W.WKV_KEEP_PADDING if args.keep_padding else 0)
+    flags = (W.WKV_KEEP_PADDING if args.keep_padding else 0) | \
+            {"auto": 0, "two-pass": W.WKV_SCORE_TWO_PASS, "single-read": W.WKV_SCORE_SINGLE_READ}[args.score]
+    st = P.DeviceState(w, device, flags=flags)
     call = W.CompressCall(st.problem, w.n_groups, w.gamma, st.q, None, st.k, st.v, st.k_out, st.v_out,
                           st.win_idx, st.tok_idx, st.n_keep, st.workspace)
     stream = torch.cuda.current_stream().cuda_stream

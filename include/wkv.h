@@ -52,6 +52,22 @@ extern "C" {
  * are a large share of the bytes written; a caller that never reads them (the decode step
  * does not) sets WKV_KEEP_PADDING and they are left as they were. */
 #define WKV_KEEP_PADDING   1
+/* How Eq. 1-2 read the keys of the scored layer.  The library uses its two-pass kernels (softmax
+ * statistics, then scores: the keys are streamed twice).  WKV_SCORE_SINGLE_READ selects the
+ * single-read kernel instead where it applies (16-bit inputs, at most 128 softmax rows per KV head,
+ * no normalisers handed over; ignored elsewhere): every key slice stays on chip between the
+ * statistics phase and the score phase and workgroups exchange the row statistics through the
+ * workspace.  On MI355X that exchange costs more than the second read it saves, so this is an
+ * option for measurements, not the default.  WKV_SCORE_TWO_PASS states the default explicitly.
+ * Results of the two agree to fp32 rounding of the normalisers.
+ * WKV_DEBUG_WAIT_GIVES_UP makes every cross-workgroup wait of the
+ * single-read kernel give up at once, which exercises its fall-back: the kernel exits normally,
+ * raises a word in the workspace, and the two-pass kernels enqueued behind it (which return at
+ * once otherwise) recompute the scores.  The same happens by itself if a wait ever runs out, e.g.
+ * when other work keeps part of the grid from being resident. */
+#define WKV_SCORE_TWO_PASS        2
+#define WKV_SCORE_SINGLE_READ     4
+#define WKV_DEBUG_WAIT_GIVES_UP   8
 
 typedef enum {
   WKV_OK = 0,
@@ -92,7 +108,7 @@ typedef struct {
   int64_t q_stride_b, q_stride_h, q_stride_t;        /* q_obs                             */
   int64_t kv_stride_b, kv_stride_h, kv_stride_t;     /* full K and V (same for both)      */
   int64_t out_stride_b, out_stride_h, out_stride_t;  /* compact K_out and V_out           */
-  int32_t flags;             /* 0, or WKV_KEEP_PADDING                                    */
+  int32_t flags;             /* 0, or an OR of the WKV_... flags above                    */
 } wkv_problem;
 
 /* Sizes derived from a problem; every output buffer below is sized by these. */

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libwkv.so")
 WKV_OK, WKV_ERR_INVALID_ARG, WKV_ERR_UNSUPPORTED, WKV_ERR_WORKSPACE, WKV_ERR_HIP = 0, -1, -2, -3, -4
 WKV_F32, WKV_BF16, WKV_F16 = 0, 1, 2
 WKV_KEEP_PADDING = 1          # Problem(flags=...): leave compact-cache rows past n_keep untouched
+WKV_SCORE_TWO_PASS, WKV_SCORE_SINGLE_READ, WKV_DEBUG_WAIT_GIVES_UP = 2, 4, 8      # Problem(flags=...)
 WKV_DECODE_KEEP_COUNT = 1     # DecodeShape(flags=...): n_valid is read but not advanced
 WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
 WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768

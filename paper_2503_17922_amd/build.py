@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libwkv.so")
-SOURCES = ["wkv_host.cpp", "wkv_api.cpp", "wkv_score.hip", "wkv_select.hip", "wkv_gather.hip",
+SOURCES = ["wkv_host.cpp", "wkv_api.cpp", "wkv_score.hip", "wkv_resident.hip", "wkv_select.hip", "wkv_gather.hip",
            "wkv_decode.hip"]
 HOST_SOURCES = ["wkv_host.cpp", "wkv_api.cpp"]          # no device code: also built for the CPU-only sanitizer test
 NOISE = "is not a recognized feature for this target"

@@ -28,11 +28,11 @@ wkv_status prepare(const wkv_problem *problem, Prepared *out) {
   return WKV_OK;
 }
 
-wkv_status check_workspace(const Shape &s, const ScorePlan &pl, int32_t n_groups, void *ws, size_t bytes,
-                           Workspace *out) {
+wkv_status check_workspace(const Shape &s, const ScorePlan &pl, const ResidentPlan &rp, int32_t n_groups, void *ws,
+                           size_t bytes, Workspace *out) {
   if (!ws) { set_error("workspace is NULL"); return WKV_ERR_WORKSPACE; }
   if (misaligned(ws, 256)) { set_error("workspace must be 256-byte aligned"); return WKV_ERR_WORKSPACE; }
-  *out = carve_workspace(s, pl, n_groups, ws);
+  *out = carve_workspace(s, pl, rp, n_groups, ws);
   if (bytes < out->bytes) {
     set_error("workspace has %zu bytes, %zu needed", bytes, out->bytes);
     return WKV_ERR_WORKSPACE;
@@ -53,14 +53,23 @@ wkv_status wkv_score(const wkv_problem *problem, const void *q_obs, const void *
   if (misaligned(q_obs, 16) || misaligned(k_first, 16)) { set_error("q_obs and k_first must be 16-byte aligned"); return WKV_ERR_INVALID_ARG; }
   if (misaligned(lse_obs, 4)) { set_error("lse_obs must be 4-byte aligned"); return WKV_ERR_INVALID_ARG; }
   const ScorePlan pl = plan_score(pr.shape, pr.bp, 1);
+  const ResidentPlan rp = plan_resident(pr.shape, pr.bp, pl, 1, problem->flags);
   Workspace ws;
-  st = check_workspace(pr.shape, pl, 1, workspace, workspace_bytes, &ws);
+  st = check_workspace(pr.shape, pl, rp, 1, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;
   GroupPtrs gp;
   std::memset(&gp, 0, sizeof(gp));
   gp.q[0] = q_obs; gp.k[0] = k_first; gp.lse[0] = lse_obs;
-  hipError_t e = launch_score(pr.shape, pr.bp, pl, gp, 1, lse_obs != nullptr, ws.partials, ws.lse, t_out, nullptr,
-                              (hipStream_t)hip_stream);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipError_t e = hipSuccess;
+  const uint32_t *only_if = nullptr;
+  if (rp.use && !lse_obs) {
+    // one read of the keys; the two-pass kernels behind it run only if a wait of it gave up
+    e = launch_resident(pr.shape, pr.bp, rp, gp, 1, ws.rk_partials, ws.lse, ws.rk_sync, t_out, nullptr, stream);
+    if (e != hipSuccess) return hip_fail(e, "wkv_score launch (single read)");
+    only_if = ws.rk_sync + RK_FAIL;
+  }
+  e = launch_score(pr.shape, pr.bp, pl, gp, 1, lse_obs != nullptr, ws.partials, ws.lse, t_out, nullptr, stream, nullptr, only_if);
   return e == hipSuccess ? WKV_OK : hip_fail(e, "wkv_score launch");
 }
 
@@ -179,8 +188,9 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
       }
   }
   const ScorePlan pl = plan_score(pr.shape, pr.bp, n_groups);
+  const ResidentPlan rp = plan_resident(pr.shape, pr.bp, pl, n_groups, problem->flags);
   Workspace ws;
-  st = check_workspace(pr.shape, pl, n_groups, workspace, workspace_bytes, &ws);
+  st = check_workspace(pr.shape, pl, rp, n_groups, workspace, workspace_bytes, &ws);
   if (st != WKV_OK) return st;
   hipStream_t stream = (hipStream_t)hip_stream;
   hipError_t e;
@@ -189,8 +199,15 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
   // With window sizes that divide the chunk length the score kernel pools its own windows
   // (Eq. 3-4 on the scores still in LDS) and only the window scores reach memory.
   float *s_pool = pl.pool_in_pass2 ? ws.s : nullptr;
+  const uint32_t *only_if = nullptr;
+  if (rp.use && !lse_obs_groups) {
+    // one read of the keys; the two-pass kernels behind it run only if a wait of it gave up
+    e = launch_resident(pr.shape, pr.bp, rp, gp, n_groups, ws.rk_partials, ws.lse, ws.rk_sync, ws.t, s_pool, stream);
+    if (e != hipSuccess) return hip_fail(e, "score launch (single read)");
+    only_if = ws.rk_sync + RK_FAIL;
+  }
   e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, lse_obs_groups != nullptr, ws.partials, ws.lse, ws.t, s_pool,
-                   stream, ev ? ev[1] : nullptr);
+                   stream, ev ? ev[1] : nullptr, only_if);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
   WKV_MARK(3)     // pooling runs inside the score or the selection kernel here: its own slot stays empty

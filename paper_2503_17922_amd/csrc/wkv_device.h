@@ -74,10 +74,10 @@ struct QStage {
   uint4 v[N];
   // Issue every load of this thread at once (independent of each other, so their latencies
   // overlap; a load-then-store loop would pay one round trip per piece).
-  __device__ __forceinline__ void load(const Shape &s, const void *qbase, int b, int h) {
+  __device__ __forceinline__ void load(const Shape &s, const void *qbase, int b, int h, int tid = threadIdx.x) {
 #pragma unroll
     for (int k = 0; k < N; ++k) {
-      const int i = threadIdx.x + k * NT;
+      const int i = tid + k * NT;
       const int l = i & 63, f = i >> 6, ks = f % KS, mt = f / KS;
       const int r = mt * 16 + (l & 15);
       v[k] = make_uint4(0u, 0u, 0u, 0u);
@@ -88,10 +88,10 @@ struct QStage {
       }
     }
   }
-  __device__ __forceinline__ void store(uint4 *qfrag) const {
+  __device__ __forceinline__ void store(uint4 *qfrag, int tid = threadIdx.x) const {
 #pragma unroll
     for (int k = 0; k < N; ++k)
-      if (threadIdx.x + k * NT < TOTAL) qfrag[threadIdx.x + k * NT] = v[k];
+      if (tid + k * NT < TOTAL) qfrag[tid + k * NT] = v[k];
   }
 };
 

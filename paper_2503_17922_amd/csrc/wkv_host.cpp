@@ -47,7 +47,12 @@ wkv_status validate(const wkv_problem *p, wkv_dims *dims) {
   if (p->head_dim != 64 && p->head_dim != 128) {
     set_error("head_dim %d is not supported (64 or 128)", p->head_dim); return WKV_ERR_UNSUPPORTED;
   }
-  if (p->flags & ~WKV_KEEP_PADDING) { set_error("unknown bits in flags (0x%x)", p->flags); return WKV_ERR_INVALID_ARG; }
+  if (p->flags & ~(WKV_KEEP_PADDING | WKV_SCORE_TWO_PASS | WKV_SCORE_SINGLE_READ | WKV_DEBUG_WAIT_GIVES_UP)) {
+    set_error("unknown bits in flags (0x%x)", p->flags); return WKV_ERR_INVALID_ARG;
+  }
+  if ((p->flags & WKV_SCORE_TWO_PASS) && (p->flags & WKV_SCORE_SINGLE_READ)) {
+    set_error("WKV_SCORE_TWO_PASS and WKV_SCORE_SINGLE_READ exclude each other"); return WKV_ERR_INVALID_ARG;
+  }
   if (p->w_obs < 1) { set_error("w_obs must be >= 1"); return WKV_ERR_INVALID_ARG; }
   const int64_t G = p->n_q_heads / p->n_kv_heads;
   if (G * p->w_obs > WKV_MAX_OBS_ROWS) {
@@ -169,23 +174,53 @@ ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   return pl;
 }
 
+// The single-read kernel applies to 16-bit inputs with at most 128 softmax rows per KV head (its
+// workgroups keep the row statistics of one row tile set in registers).  It is taken only when the
+// caller asks for it: on MI355X the exchange of the row statistics between workgroups costs more
+// than the second read of the keys it saves (measured at the 32K configuration: 0.57 ms against
+// 0.21 ms for the two passes), so the library never chooses it by itself.
+ResidentPlan plan_resident(const Shape &s, const BatchParams &bp, const ScorePlan &plan, int32_t n_groups, int32_t flags) {
+  ResidentPlan rp;
+  std::memset(&rp, 0, sizeof(rp));
+  rp.m_pad = plan.m_pad;
+  int64_t per_group = 0;
+  for (int32_t b = 0; b < s.B; ++b) {
+    const int64_t nsl = ceil_div(bp.seq[b].L, RK_SLICE);
+    per_group += nsl * s.Hkv;
+    if (nsl > rp.nsl_max) rp.nsl_max = (int32_t)nsl;
+  }
+  const int64_t items = per_group * n_groups;
+  rp.items_per_group = (int32_t)per_group;
+  rp.n_items = (int32_t)items;
+  // a wait that is still unanswered after this many polls (tens of milliseconds) gives up
+  rp.spin_limit = (flags & WKV_DEBUG_WAIT_GIVES_UP) ? 0 : (1 << 16);
+  const bool can = plan.mfma && plan.m_pad <= 128 && s.t_stride > 0 && items < (int64_t)1 << 30;
+  rp.use = can && (flags & WKV_SCORE_SINGLE_READ);
+  return rp;
+}
+
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base) {
+Workspace carve_workspace(const Shape &s, const ScorePlan &plan, const ResidentPlan &rp, int32_t n_groups, void *base) {
   Workspace w;
   const size_t rows = (size_t)n_groups * s.B * s.Hkv;
   const size_t part = align256(rows * plan.m_pad * plan.n_chunks1 * sizeof(float2));
   const size_t tb = align256(rows * (size_t)(s.t_stride > 0 ? s.t_stride : 1) * sizeof(float));
   const size_t sb = align256(rows * (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(float));
   const size_t lb = align256(rows * plan.m_pad * sizeof(float));
+  // single-read kernel: the (m, z) partials of every slice and the synchronisation words
+  const size_t rkp = rp.use ? align256(rows * (size_t)rp.nsl_max * rp.m_pad * sizeof(unsigned long long)) : 0;
+  const size_t rks = rp.use ? align256((RK_GLOBAL_WORDS + rows * RK_SYNC_WORDS) * sizeof(uint32_t)) : 0;
   w.t_offset = part;
   w.s_offset = part + tb;
-  w.bytes = part + tb + sb + lb;
+  w.bytes = part + tb + sb + lb + rkp + rks;
   char *b = (char *)base;          // a null base asks for the sizes only: no pointer is formed from it
   w.partials = b ? (float2 *)b : nullptr;
   w.t = b ? (float *)(b + w.t_offset) : nullptr;
   w.s = b ? (float *)(b + w.s_offset) : nullptr;
   w.lse = b ? (float *)(b + part + tb + sb) : nullptr;
+  w.rk_partials = b && rp.use ? (unsigned long long *)(b + part + tb + sb + lb) : nullptr;
+  w.rk_sync = b && rp.use ? (uint32_t *)(b + part + tb + sb + lb + rkp) : nullptr;
   return w;
 }
 
@@ -256,7 +291,7 @@ size_t wkv_workspace_bytes(const wkv_problem *problem, int32_t n_groups) {
   Shape s; BatchParams bp;
   fill_shape(problem, dm, &s, &bp);
   ScorePlan pl = plan_score(s, bp, n_groups);
-  return carve_workspace(s, pl, n_groups, nullptr).bytes;
+  return carve_workspace(s, pl, plan_resident(s, bp, pl, n_groups, problem->flags), n_groups, nullptr).bytes;
 }
 
 wkv_status wkv_get_workspace_layout(const wkv_problem *problem, int32_t n_groups, wkv_workspace_layout *layout) {
@@ -268,7 +303,7 @@ wkv_status wkv_get_workspace_layout(const wkv_problem *problem, int32_t n_groups
   Shape s; BatchParams bp;
   fill_shape(problem, dm, &s, &bp);
   const ScorePlan pl = plan_score(s, bp, n_groups);
-  const Workspace w = carve_workspace(s, pl, n_groups, nullptr);
+  const Workspace w = carve_workspace(s, pl, plan_resident(s, bp, pl, n_groups, problem->flags), n_groups, nullptr);
   layout->t_offset = w.t_offset;
   layout->s_offset = w.s_offset;
   layout->s_written = pl.pool_in_pass2 ? 1 : 0;

@@ -73,11 +73,31 @@ struct ScorePlan {
   bool pool_in_pass2;          // MFMA path: pass 2 can pool its chunk's windows (every window size divides 128)
 };
 
+// ---- single-read score kernel ("resident keys") ----------------------------------------------------
+constexpr int32_t RK_SLICE = 256;        // keys a workgroup holds in registers between its two phases
+// Synchronisation words in the workspace (uint32, cleared at the start of every call): a few
+// global ones, then RK_SYNC_WORDS per (group, sequence, KV head) row.
+constexpr int32_t RK_GLOBAL_WORDS = 4;
+constexpr int32_t RK_FAIL = 0;           // global: a bounded wait ran out; the two-pass kernels redo the scores
+constexpr int32_t RK_SYNC_WORDS = 4;
+constexpr int32_t RK_ARRIVED = 0;        // per row: slices whose phase-1 partials are in the workspace
+constexpr int32_t RK_READY = 1;          // per row: the normalisers of the row are published
+
+struct ResidentPlan {
+  int32_t use;                           // the call takes the single-read kernel
+  int32_t n_items, items_per_group;      // slices in the call / in one group
+  int32_t nsl_max;                       // most slices of any row
+  int32_t m_pad;
+  int32_t spin_limit;                    // polls before a waiting workgroup gives up
+};
+
 struct Workspace {
   float2 *partials;   // [n_groups][B][Hkv][m_pad][n_chunks1] (running max, sum) in base 2
   float *lse;         // [n_groups][B][Hkv][m_pad] base-2 log-sum-exp of every softmax row
   float *t;           // [n_groups][B][Hkv][t_stride]
   float *s;           // [n_groups][B][Hkv][nw_max]
+  unsigned long long *rk_partials;   // [rows][nsl_max][m_pad] (m, z) of every slice (single-read kernel)
+  uint32_t *rk_sync;                 // [RK_GLOBAL_WORDS + rows * RK_SYNC_WORDS]
   size_t t_offset, s_offset;   // byte offsets of t and s from the base
   size_t bytes;
 };
@@ -87,14 +107,21 @@ void set_error(const char *fmt, ...);
 wkv_status validate(const wkv_problem *p, wkv_dims *dims);
 void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParams *bp);
 ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups);
-Workspace carve_workspace(const Shape &s, const ScorePlan &plan, int32_t n_groups, void *base);
+ResidentPlan plan_resident(const Shape &s, const BatchParams &bp, const ScorePlan &plan, int32_t n_groups, int32_t flags);
+Workspace carve_workspace(const Shape &s, const ScorePlan &plan, const ResidentPlan &rp, int32_t n_groups, void *base);
 
 // ---- launchers (one per kernel family) ----------------------------------------------------
 // All return hipSuccess or the launch error. Pointers are device pointers unless noted.
 // `mid`, if not null, is recorded between the stats pass and the score pass.
+// `only_if`, if not null, points to a device word: the kernels return at once unless it is non-zero.
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &plan,
                         const GroupPtrs &gp, int32_t n_groups, bool have_lse, float2 *partials, float *lse,
-                        float *t_out, float *s_pool, hipStream_t stream, hipEvent_t mid = nullptr);
+                        float *t_out, float *s_pool, hipStream_t stream, hipEvent_t mid = nullptr,
+                        const uint32_t *only_if = nullptr);
+// Clears the synchronisation words, then the single-read score kernel (Eq. 1-2, pooled if s_pool).
+hipError_t launch_resident(const Shape &s, const BatchParams &bp, const ResidentPlan &rp, const GroupPtrs &gp,
+                           int32_t n_groups, unsigned long long *partials, float *lse, uint32_t *sync, float *t_out,
+                           float *s_pool, hipStream_t stream);
 hipError_t launch_pool(const Shape &s, const BatchParams &bp, int32_t n_groups, const float *t,
                        float *s_out, hipStream_t stream);
 hipError_t launch_topk(const Shape &s, const BatchParams &bp, const GroupK &gk, int32_t n_groups, const float *sc,

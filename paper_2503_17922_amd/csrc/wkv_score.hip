@@ -39,8 +39,9 @@ template <> struct Elem<float> {
 constexpr int FOLD_THREADS = 256;
 
 __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(Shape s, ScorePlan pl, const float2 *__restrict__ partials,
-                                                            float *__restrict__ lse) {
+                                                            float *__restrict__ lse, const uint32_t *__restrict__ only_if) {
   __shared__ float2 part_s[FOLD_THREADS];
+  if (only_if && *only_if == 0u) return;
   const int64_t row = (int64_t)blockIdx.y * s.B * s.Hkv + blockIdx.x;
   // TPR threads share a row; rows are handled in passes of FOLD_THREADS / TPR
   const int TPR = pl.m_pad >= 128 ? 2 : (pl.m_pad >= 64 ? 4 : 8);
@@ -204,10 +205,14 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
                                                                    ScorePlan pl, float2 *__restrict__ partials,
                                                                    const float *__restrict__ lse_g,
                                                                    float *__restrict__ t_out,
-                                                                   float *__restrict__ s_pool) {
+                                                                   float *__restrict__ s_pool,
+                                                                   const uint32_t *__restrict__ only_if) {
   constexpr int KS = D / 32;
   constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
   constexpr int NT = MF_THREADS * HV;                 // threads of the workgroup
+  // Launched behind the single-read kernel as its fall-back: nothing to do unless that kernel
+  // raised the word (uniform over the grid).
+  if (only_if && *only_if == 0u) return;
   constexpr int MTT = MT * HV;                        // row tiles of the workgroup
   constexpr int TS_LEN = MAX_CHUNK2 + 256;            // token scores of a chunk + the scrap area
   __shared__ uint4 qfrag[MTT * KS * 64];
@@ -463,7 +468,7 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
 template <int D, int MT, int HV, bool F16>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                               int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
-                              float *s_pool, hipStream_t stream, hipEvent_t mid) {
+                              float *s_pool, hipStream_t stream, hipEvent_t mid, const uint32_t *only_if) {
   dim3 block(MF_THREADS * HV);
   hipError_t e;
   if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
@@ -471,19 +476,19 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
     if (s.t_stride <= 0) return hipSuccess;
   } else {
     dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1, F16>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1, F16>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool, only_if);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
     if (!pl.fold_in_pass2) {
-      hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+      hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse, only_if);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   }
   ScorePlan pl2 = pl;
   if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2, F16>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2, F16>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool, only_if);
   return hipGetLastError();
 }
 
@@ -504,7 +509,7 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
-    hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse);
+    hipLaunchKernelGGL(fold_kernel, dim3(s.B * s.Hkv, n_groups), dim3(FOLD_THREADS), 0, stream, s, pl, partials, lse, (const uint32_t *)nullptr);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   const size_t lds = ((size_t)s.M * D + s.M) * sizeof(float);
@@ -520,14 +525,14 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                         int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out, float *s_pool,
-                        hipStream_t stream, hipEvent_t mid) {
+                        hipStream_t stream, hipEvent_t mid, const uint32_t *only_if) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
     const bool f16 = s.dtype == WKV_F16;
 #define WKV_MFMA_CASE(DD, MM, HH)                                                                              \
   if (s.d == DD && mt <= MM * HH)                                                                              \
-    return f16 ? launch_mfma<DD, MM, HH, true>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid) \
-               : launch_mfma<DD, MM, HH, false>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid);
+    return f16 ? launch_mfma<DD, MM, HH, true>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if) \
+               : launch_mfma<DD, MM, HH, false>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if);
     WKV_MFMA_CASE(128, 1, 1) WKV_MFMA_CASE(128, 2, 1) WKV_MFMA_CASE(128, 4, 1) WKV_MFMA_CASE(128, 8, 1)
     WKV_MFMA_CASE(64, 1, 1) WKV_MFMA_CASE(64, 2, 1) WKV_MFMA_CASE(64, 4, 1) WKV_MFMA_CASE(64, 8, 1)
     WKV_MFMA_CASE(128, 8, 2) WKV_MFMA_CASE(64, 8, 2)      // 129..256 rows: two halves of 8 row tiles

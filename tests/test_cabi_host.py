@@ -70,7 +70,8 @@ def test_dims_of_the_named_configurations():
     (dict(kv_strides=(8 * 4096 * 128, 4096 * 128, 100)), W.WKV_ERR_INVALID_ARG),
     (dict(kv_strides=(8 * 4096 * 132, 4096 * 132, 132)), W.WKV_ERR_INVALID_ARG),   # not 16-byte rows
     (dict(seq_len=[300000], win=[8], k_windows=[1]), W.WKV_ERR_UNSUPPORTED),       # too many windows
-    (dict(flags=2), W.WKV_ERR_INVALID_ARG),                                        # unknown flag bit
+    (dict(flags=64), W.WKV_ERR_INVALID_ARG),                                       # unknown flag bit
+    (dict(flags=W.WKV_SCORE_TWO_PASS | W.WKV_SCORE_SINGLE_READ), W.WKV_ERR_INVALID_ARG),   # they exclude each other
 ])
 def test_invalid_problems_are_rejected_on_the_host(kw, status):
     with pytest.raises(W.WkvError) as e:

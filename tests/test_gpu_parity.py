@@ -40,7 +40,7 @@ def batched_intermediates(st):
             view(lay.s_offset, d.nw_max) if lay.s_written else None)
 
 
-def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, stage_groups=None, as_f16=False):
+def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, stage_groups=None, as_f16=False, flags=0):
     """One wkv_compress_groups call checked against the oracle.
 
     n_oracle: how many (group, b, h) problems the oracle recomputes (None = all).
@@ -51,7 +51,7 @@ def run_and_check(w: S.Workload, device, n_oracle=None, n_gather_cpu=None, stage
     batched call itself computed (its s, or its t when it pools in the selection kernel, read back
     from the workspace) are compared element by element.
     """
-    st = P.DeviceState(w, device, as_f16=as_f16)
+    st = P.DeviceState(w, device, as_f16=as_f16, flags=flags)
     print(f"[{w.name}] L={w.seq_len} win={w.win} p={w.top_p} k={w.k_windows} groups={w.n_groups}x{w.gamma} "
           f"ws={st.ws_bytes >> 10} KiB", flush=True)
     if not as_f16 and w.dtype != "f16":
@@ -308,6 +308,53 @@ def test_single_group_entry_point(device):
                          st.n_keep[0], st.workspace)
     torch.cuda.synchronize()
     assert torch.equal(st.tok_idx, ref.tok_idx) and torch.equal(st.k_out[2], ref.k_out[2])
+
+
+# ---------------------------------------------------------------------------------------
+# the single-read score kernel (keys stay on chip between the statistics and the score phase)
+# ---------------------------------------------------------------------------------------
+SINGLE_READ_CASES = [
+    dict(),                                                               # 3 slices per row, ragged tail
+    dict(seq_len=[1000, 16, 333, 2048], win=[8, 8, 32, 128], top_p=[4, 8, 1, 64], k_windows=[20, 0, 3, 5]),
+    dict(seq_len=[16], k_windows=[0]),                                    # no review context at all
+    dict(seq_len=[17], win=[8], k_windows=[1]),                           # one review token
+    dict(seq_len=[272, 256, 528], win=[8, 16, 8], top_p=[8, 8, 3], k_windows=[5, 7, 9]),   # review context ends exactly on slice boundaries
+    dict(win=[24], top_p=[7], k_windows=[9]),                             # token scores to memory, pooled by the selection kernel
+    dict(n_q_heads=6, n_kv_heads=2, w_obs=5),                             # 15 softmax rows
+    dict(n_q_heads=4, n_kv_heads=4, w_obs=1),
+    dict(head_dim=64, seq_len=[3000], k_windows=[40]),
+    dict(n_groups=3, gamma=1, seq_len=[9000, 700, 4097], win=[16, 8, 16], top_p=[8, 8, 16], k_windows=[40, 9, 31]),   # 36 slices per row
+    dict(n_q_heads=16, n_kv_heads=2, w_obs=32, seq_len=[1500]),           # 256 rows: not covered by this kernel, the flag is ignored
+]
+
+
+@pytest.mark.parametrize("kw", SINGLE_READ_CASES)
+def test_single_read_kernel(kw, device):
+    run_and_check(_mini(**kw), device, flags=W.WKV_SCORE_SINGLE_READ)
+
+
+@pytest.mark.parametrize("kw", [SINGLE_READ_CASES[1], SINGLE_READ_CASES[5], SINGLE_READ_CASES[9]])
+def test_single_read_kernel_gives_up_and_the_two_pass_kernels_take_over(kw, device):
+    # every cross-workgroup wait of the single-read kernel is told to give up at once (a limit of
+    # zero polls, set from the host): the kernel exits normally, raises its fall-back word, and
+    # the two-pass kernels enqueued behind it recompute the scores
+    w = _mini(**kw)
+    run_and_check(w, device, flags=W.WKV_SCORE_SINGLE_READ | W.WKV_DEBUG_WAIT_GIVES_UP)
+    ref = P.DeviceState(w, device, flags=W.WKV_SCORE_TWO_PASS); ref.compress()
+    st = P.DeviceState(w, device, flags=W.WKV_SCORE_SINGLE_READ | W.WKV_DEBUG_WAIT_GIVES_UP); st.compress()
+    assert torch.equal(ref.tok_idx, st.tok_idx) and torch.equal(ref.win_idx, st.win_idx)      # the very same kernels produced both
+
+
+def test_single_read_and_two_pass_agree_at_full_size(device):
+    w = S.make_workload("c4")
+    a = P.DeviceState(w, device, flags=W.WKV_SCORE_SINGLE_READ); a.compress()
+    _, s_a = batched_intermediates(a)
+    b = P.DeviceState(w, device, flags=W.WKV_SCORE_TWO_PASS); b.compress()
+    _, s_b = batched_intermediates(b)
+    nw = w.n_windows(0)
+    np.testing.assert_allclose(s_a[..., :nw], s_b[..., :nw], rtol=1e-5)
+    same = (a.win_idx == b.win_idx).all(dim=-1).float().mean().item()
+    assert same > 0.9, f"only {same:.2f} of the rows select the same windows"
 
 
 def test_large_logits_are_stable(device):
