@@ -206,20 +206,12 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
     if (e != hipSuccess) return hip_fail(e, "score launch (single read)");
     only_if = ws.rk_sync + RK_FAIL;
   }
-  // Where the window scores of a row fit the score kernel's LDS, the workgroup that finishes the
-  // row last selects its windows (Section 2.2.1) in the same launch.  Not with budgets per group
-  // (their table does not fit beside the other kernel arguments), not without the statistics pass
-  // (it clears the arrival tickets), not behind the single-read kernel.
-  const bool select_in_score = pl.topk_in_pass2 && s_pool && !lse_obs_groups && !gk.in_use && !only_if &&
-                               pr.shape.t_stride > 0;      // (no review context anywhere: no score pass is launched)
-  const TailArgs tail = {ws.tickets, win_idx_out, tok_idx_out, n_keep_out};
   e = launch_score(pr.shape, pr.bp, pl, gp, n_groups, lse_obs_groups != nullptr, ws.partials, ws.lse, ws.t, s_pool,
-                   stream, ev ? ev[1] : nullptr, only_if, select_in_score ? &tail : nullptr);
+                   stream, ev ? ev[1] : nullptr, only_if);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
   WKV_MARK(3)     // pooling runs inside the score or the selection kernel here: its own slot stays empty
-  if (select_in_score) e = hipSuccess;
-  else if (s_pool) e = launch_topk(pr.shape, pr.bp, gk, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
+  if (s_pool) e = launch_topk(pr.shape, pr.bp, gk, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
   else e = launch_select(pr.shape, pr.bp, gk, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "select launch");
   WKV_MARK(4)

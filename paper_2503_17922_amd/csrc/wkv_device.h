@@ -24,28 +24,6 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// ---- what workgroups of one launch exchange through memory ------------------------------------
-// Device-scope relaxed atomics: the store goes through to memory, the load fetches from there, no
-// cache is written back or invalidated as a whole.  A writer orders "data, then flag / ticket" by
-// waiting for the acknowledgement of its stores (wait_vmem) before the next operation.
-__device__ __forceinline__ void store_agent(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float load_agent(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_agent(unsigned long long *p, unsigned long long v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long load_agent(const unsigned long long *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t load_agent(const uint32_t *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// All vector-memory operations of this wave issued so far have been acknowledged.
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // Merge (m2, z2) into (m, z): both describe sum 2^(v - m) over disjoint key sets.
 __device__ __forceinline__ void merge_stats(float &m, float &z, float m2, float z2) {
   const float mn = fmaxf(m, m2);

@@ -171,8 +171,6 @@ ScorePlan plan_score(const Shape &s, const BatchParams &bp, int32_t n_groups) {
   // chunks are multiples of 128 keys: windows never straddle two workgroups when win divides 128
   pl.pool_in_pass2 = pl.mfma;
   for (int32_t b = 0; b < s.B; ++b) pl.pool_in_pass2 = pl.pool_in_pass2 && (128 % bp.seq[b].win == 0);
-  // the selecting workgroup keeps the row's window scores as keys where the chunk's token scores were
-  pl.topk_in_pass2 = pl.pool_in_pass2 && s.nw_max <= MAX_CHUNK2;
   return pl;
 }
 
@@ -210,21 +208,19 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, const ResidentP
   const size_t tb = align256(rows * (size_t)(s.t_stride > 0 ? s.t_stride : 1) * sizeof(float));
   const size_t sb = align256(rows * (size_t)(s.nw_max > 0 ? s.nw_max : 1) * sizeof(float));
   const size_t lb = align256(rows * plan.m_pad * sizeof(float));
-  const size_t tk = align256(rows * sizeof(uint32_t));
   // single-read kernel: the (m, z) partials of every slice and the synchronisation words
   const size_t rkp = rp.use ? align256(rows * (size_t)rp.nsl_max * rp.m_pad * sizeof(unsigned long long)) : 0;
   const size_t rks = rp.use ? align256((RK_GLOBAL_WORDS + rows * RK_SYNC_WORDS) * sizeof(uint32_t)) : 0;
   w.t_offset = part;
   w.s_offset = part + tb;
-  w.bytes = part + tb + sb + lb + tk + rkp + rks;
+  w.bytes = part + tb + sb + lb + rkp + rks;
   char *b = (char *)base;          // a null base asks for the sizes only: no pointer is formed from it
   w.partials = b ? (float2 *)b : nullptr;
   w.t = b ? (float *)(b + w.t_offset) : nullptr;
   w.s = b ? (float *)(b + w.s_offset) : nullptr;
   w.lse = b ? (float *)(b + part + tb + sb) : nullptr;
-  w.tickets = b ? (uint32_t *)(b + part + tb + sb + lb) : nullptr;
-  w.rk_partials = b && rp.use ? (unsigned long long *)(b + part + tb + sb + lb + tk) : nullptr;
-  w.rk_sync = b && rp.use ? (uint32_t *)(b + part + tb + sb + lb + tk + rkp) : nullptr;
+  w.rk_partials = b && rp.use ? (unsigned long long *)(b + part + tb + sb + lb) : nullptr;
+  w.rk_sync = b && rp.use ? (uint32_t *)(b + part + tb + sb + lb + rkp) : nullptr;
   return w;
 }
 

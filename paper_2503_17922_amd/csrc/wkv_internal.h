@@ -71,14 +71,6 @@ struct ScorePlan {
   bool mfma;                   // bf16 MFMA kernels (else the generic ones)
   bool fold_in_pass2;          // MFMA path: pass 2 folds the pass-1 partials itself (few chunks per row)
   bool pool_in_pass2;          // MFMA path: pass 2 can pool its chunk's windows (every window size divides 128)
-  bool topk_in_pass2;          // ... and the workgroup that finishes a row last can select its windows (they fit its LDS)
-};
-
-// Selection in the tail of the score pass: per-row arrival tickets (cleared by the statistics
-// pass) and the selection outputs.  All null: the pass only scores.
-struct TailArgs {
-  uint32_t *tickets;          // [n_groups][B][Hkv]
-  int32_t *win_idx, *tok_idx, *n_keep;
 };
 
 // ---- single-read score kernel ("resident keys") ----------------------------------------------------
@@ -104,7 +96,6 @@ struct Workspace {
   float *lse;         // [n_groups][B][Hkv][m_pad] base-2 log-sum-exp of every softmax row
   float *t;           // [n_groups][B][Hkv][t_stride]
   float *s;           // [n_groups][B][Hkv][nw_max]
-  uint32_t *tickets;                 // [rows] arrival tickets of the score pass (selection in its tail)
   unsigned long long *rk_partials;   // [rows][nsl_max][m_pad] (m, z) of every slice (single-read kernel)
   uint32_t *rk_sync;                 // [RK_GLOBAL_WORDS + rows * RK_SYNC_WORDS]
   size_t t_offset, s_offset;   // byte offsets of t and s from the base
@@ -126,7 +117,7 @@ Workspace carve_workspace(const Shape &s, const ScorePlan &plan, const ResidentP
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &plan,
                         const GroupPtrs &gp, int32_t n_groups, bool have_lse, float2 *partials, float *lse,
                         float *t_out, float *s_pool, hipStream_t stream, hipEvent_t mid = nullptr,
-                        const uint32_t *only_if = nullptr, const TailArgs *tail = nullptr);
+                        const uint32_t *only_if = nullptr);
 // Clears the synchronisation words, then the single-read score kernel (Eq. 1-2, pooled if s_pool).
 hipError_t launch_resident(const Shape &s, const BatchParams &bp, const ResidentPlan &rp, const GroupPtrs &gp,
                            int32_t n_groups, unsigned long long *partials, float *lse, uint32_t *sync, float *t_out,

@@ -25,7 +25,6 @@
 //     thread-per-key for the scores, the other operand broadcast from LDS.
 #include "wkv_device.h"
 #include "wkv_pool.h"
-#include "wkv_topk.h"
 
 namespace wkv {
 
@@ -207,7 +206,7 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
                                                                    const float *__restrict__ lse_g,
                                                                    float *__restrict__ t_out,
                                                                    float *__restrict__ s_pool,
-                                                                   const uint32_t *__restrict__ only_if, TailArgs tail) {
+                                                                   const uint32_t *__restrict__ only_if) {
   constexpr int KS = D / 32;
   constexpr int STEP = 16 * MF_KT;                    // keys per wave iteration
   constexpr int NT = MF_THREADS * HV;                 // threads of the workgroup
@@ -223,7 +222,6 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
   // every wait for keys also wait for store acknowledgements.
   __shared__ __attribute__((aligned(16))) float t_s[PASS == 2 ? HV * TS_LEN : 1];
   __shared__ float lse_s[PASS == 2 ? MTT * 16 : 1];
-  __shared__ int last_s;
 
   // Pass 2 walks the work items in the opposite order of pass 1: the keys pass 1 read last
   // are the ones most likely still held by the memory-side cache.
@@ -243,37 +241,14 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
   const int limit = PASS == 1 ? L : n_review;         // keys that matter to this pass
   float *trow = PASS == 2 ? t_out + row * s.t_stride : nullptr;
 
-  // Selection in the tail of pass 2 (Section 2.2.1): every workgroup that scores a chunk of the row
-  // takes a ticket when its window scores are out; the one that draws the last ticket has them all
-  // and selects.  Nobody waits.  A row without review context has no scoring workgroup: its first
-  // chunk takes the only ticket.
-  const int n_tickets = max((n_review + chunk - 1) / chunk, 1);
-  auto ticket_and_select = [&]() {
-    if constexpr (PASS != 2) return;
-    wait_vmem();                                      // this workgroup's window scores have reached memory
-    __syncthreads();
-    if (threadIdx.x == 0)
-      last_s = __hip_atomic_fetch_add(tail.tickets + row, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(n_tickets - 1);
-    __syncthreads();
-    if (!last_s) return;
-    const SeqParam sp = bp.seq[b];
-    const int nw = (n_review + sp.win - 1) / sp.win;
-    uint32_t *keys = (uint32_t *)t_s;                 // the chunk's token scores are no longer needed
-    const float *srow = s_pool + row * s.nw_max;
-    for (int w = threadIdx.x; w < nw; w += NT) keys[w] = float_to_key(load_agent(srow + w));
-    __syncthreads();
-    topk_body<NT>(s, sp, keys, row, tail.win_idx, tail.tok_idx, tail.n_keep);
-  };
   if (PASS == 2) {
     const int cend_fill = min(c0 + chunk, s.t_stride);
     if (c0 >= n_review) {
       if (!s_pool)
         for (int j = c0 + threadIdx.x; j < cend_fill; j += NT) trow[j] = 0.0f;
-      if (tail.tickets && c0 == 0) ticket_and_select();
       return;
     }
   }
-  if (PASS == 1 && tail.tickets && bx == 0 && threadIdx.x == 0) tail.tickets[row] = 0u;   // for the score pass
   if (PASS == 1 && c0 >= L) {                         // a chunk past the end of a short sequence
     for (int r = threadIdx.x; r < pl.m_pad; r += NT)
       partials[(row * pl.m_pad + r) * pl.n_chunks1 + bx] = make_float2(-INFINITY, 0.0f);
@@ -458,12 +433,8 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
       const SeqParam sp = bp.seq[b];
       const int w0 = c0 / sp.win, w1 = (cend + sp.win - 1) / sp.win;
       float *srow = s_pool + row * s.nw_max;
-      if (tail.tickets) {                              // the selecting workgroup reads them in this launch
-        for (int w = w0 + threadIdx.x; w < w1; w += NT) store_agent(srow + w, pool_window(t_s - c0, w, sp.win, n_review, sp.p));
-        ticket_and_select();
-      } else {
-        for (int w = w0 + threadIdx.x; w < w1; w += NT) srow[w] = pool_window(t_s - c0, w, sp.win, n_review, sp.p);
-      }
+      for (int w = w0 + threadIdx.x; w < w1; w += NT)
+        srow[w] = pool_window(t_s - c0, w, sp.win, n_review, sp.p);
     } else {
       const int cend_fill = min(c0 + chunk, s.t_stride);
       for (int j = c0 + threadIdx.x; j < cend_fill; j += NT) trow[j] = j < cend ? t_s[j - c0] : 0.0f;
@@ -497,7 +468,7 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
 template <int D, int MT, int HV, bool F16>
 static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                               int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out,
-                              float *s_pool, hipStream_t stream, hipEvent_t mid, const uint32_t *only_if, const TailArgs &tail) {
+                              float *s_pool, hipStream_t stream, hipEvent_t mid, const uint32_t *only_if) {
   dim3 block(MF_THREADS * HV);
   hipError_t e;
   if (have_lse) {                                      // no statistics pass: pass 2 reads the caller's normalisers
@@ -505,7 +476,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
     if (s.t_stride <= 0) return hipSuccess;
   } else {
     dim3 g1(pl.n_chunks1, s.B * s.Hkv, n_groups);
-    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1, F16>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool, only_if, tail);
+    hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 1, F16>), g1, block, 0, stream, s, bp, gp, pl, partials, lse, t_out, s_pool, only_if);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (mid && (e = hipEventRecord(mid, stream)) != hipSuccess) return e;
     if (s.t_stride <= 0) return hipSuccess;
@@ -517,7 +488,7 @@ static hipError_t launch_mfma(const Shape &s, const BatchParams &bp, const Score
   ScorePlan pl2 = pl;
   if (have_lse) pl2.fold_in_pass2 = false;
   dim3 g2(pl.n_chunks2, s.B * s.Hkv, n_groups);
-  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2, F16>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool, only_if, tail);
+  hipLaunchKernelGGL((score_mfma_kernel<D, MT, HV, 2, F16>), g2, block, 0, stream, s, bp, gp, pl2, partials, lse, t_out, s_pool, only_if);
   return hipGetLastError();
 }
 
@@ -554,16 +525,14 @@ static hipError_t launch_generic(const Shape &s, const BatchParams &bp, const Sc
 
 hipError_t launch_score(const Shape &s, const BatchParams &bp, const ScorePlan &pl, const GroupPtrs &gp,
                         int32_t n_groups, bool have_lse, float2 *partials, float *lse, float *t_out, float *s_pool,
-                        hipStream_t stream, hipEvent_t mid, const uint32_t *only_if, const TailArgs *tail_in) {
-  TailArgs tail = {nullptr, nullptr, nullptr, nullptr};
-  if (tail_in && !have_lse && s_pool && pl.topk_in_pass2) tail = *tail_in;    // needs the statistics pass (it clears the tickets)
+                        hipStream_t stream, hipEvent_t mid, const uint32_t *only_if) {
   if (pl.mfma) {
     const int mt = pl.m_pad / 16;
     const bool f16 = s.dtype == WKV_F16;
 #define WKV_MFMA_CASE(DD, MM, HH)                                                                              \
   if (s.d == DD && mt <= MM * HH)                                                                              \
-    return f16 ? launch_mfma<DD, MM, HH, true>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if, tail) \
-               : launch_mfma<DD, MM, HH, false>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if, tail);
+    return f16 ? launch_mfma<DD, MM, HH, true>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if) \
+               : launch_mfma<DD, MM, HH, false>(s, bp, pl, gp, n_groups, have_lse, partials, lse, t_out, s_pool, stream, mid, only_if);
     WKV_MFMA_CASE(128, 1, 1) WKV_MFMA_CASE(128, 2, 1) WKV_MFMA_CASE(128, 4, 1) WKV_MFMA_CASE(128, 8, 1)
     WKV_MFMA_CASE(64, 1, 1) WKV_MFMA_CASE(64, 2, 1) WKV_MFMA_CASE(64, 4, 1) WKV_MFMA_CASE(64, 8, 1)
     WKV_MFMA_CASE(128, 8, 2) WKV_MFMA_CASE(64, 8, 2)      // 129..256 rows: two halves of 8 row tiles

@@ -7,7 +7,7 @@ extern "C" int wkv_stub_launches = 0;
 
 namespace wkv {
 hipError_t launch_score(const Shape &, const BatchParams &, const ScorePlan &, const GroupPtrs &, int32_t, bool, float2 *,
-                        float *, float *, float *, hipStream_t, hipEvent_t, const uint32_t *, const TailArgs *) { ++wkv_stub_launches; return hipSuccess; }
+                        float *, float *, float *, hipStream_t, hipEvent_t, const uint32_t *) { ++wkv_stub_launches; return hipSuccess; }
 hipError_t launch_resident(const Shape &, const BatchParams &, const ResidentPlan &, const GroupPtrs &, int32_t,
                            unsigned long long *, float *, uint32_t *, float *, float *, hipStream_t) { ++wkv_stub_launches; return hipSuccess; }
 hipError_t launch_pool(const Shape &, const BatchParams &, int32_t, const float *, float *, hipStream_t) { ++wkv_stub_launches; return hipSuccess; }
