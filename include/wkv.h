@@ -269,12 +269,12 @@ wkv_status wkv_compress_groups(const wkv_problem *problem, int32_t n_groups, int
  * stream, and reports each kernel's duration.  It creates and destroys HIP events and blocks
  * the calling thread, so it is for benchmarks and profiling, not for serving.
  *   stage_ms_out  host float [WKV_N_STAGES]: milliseconds of, in order, the softmax-statistics
- *                 pass (Eq. 1; with lse_obs_groups, the conversion of the given normalisers),
- *                 the score pass (Eq. 1-2), window pooling (Eq. 3-4; 0 here, because
- *                 this call pools inside the selection kernel), pooling + top-k selection
- *                 (2.2.1) and the shared-index gather (2.2.2).
+ *                 pass (Eq. 1; 0 with lse_obs_groups; with WKV_SCORE_SINGLE_READ the single-read
+ *                 kernel, which then covers Eq. 1-2), the score pass (Eq. 1-2, and Eq. 3-4 where it
+ *                 pools its own windows), the selection kernel (2.2.1, and Eq. 3-4 otherwise) and
+ *                 the shared-index gather (2.2.2).
  */
-#define WKV_N_STAGES 5
+#define WKV_N_STAGES 4
 wkv_status wkv_compress_groups_profiled(const wkv_problem *problem, int32_t n_groups, int32_t gamma,
                                         const void *const *q_obs_groups,
                                         const float *const *lse_obs_groups,

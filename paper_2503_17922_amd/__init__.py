@@ -21,8 +21,8 @@ WKV_SCORE_TWO_PASS, WKV_SCORE_SINGLE_READ, WKV_DEBUG_WAIT_GIVES_UP = 2, 4, 8    
 WKV_DECODE_KEEP_COUNT = 1     # DecodeShape(flags=...): n_valid is read but not advanced
 WKV_MAX_BATCH, WKV_MAX_GROUPS, WKV_MAX_LAYERS, WKV_MAX_WIN = 64, 64, 64, 128
 WKV_MAX_OBS_ROWS, WKV_MAX_WINDOWS = 256, 32768
-WKV_N_STAGES = 5
-STAGE_NAMES = ("score_pre", "score", "window_pool", "topk_windows", "gather")
+WKV_N_STAGES = 4
+STAGE_NAMES = ("score_stats", "score", "select", "gather")
 
 EXPORTS = ("wkv_get_dims", "wkv_workspace_bytes", "wkv_get_workspace_layout", "wkv_score", "wkv_window_pool",
            "wkv_topk_windows", "wkv_gather_group", "wkv_compress_group", "wkv_compress_groups",

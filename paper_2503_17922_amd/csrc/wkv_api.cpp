@@ -210,14 +210,13 @@ static wkv_status compress_impl(const wkv_problem *problem, int32_t n_groups, in
                    stream, ev ? ev[1] : nullptr, only_if);
   if (e != hipSuccess) return hip_fail(e, "score launch");
   WKV_MARK(2)
-  WKV_MARK(3)     // pooling runs inside the score or the selection kernel here: its own slot stays empty
   if (s_pool) e = launch_topk(pr.shape, pr.bp, gk, n_groups, ws.s, win_idx_out, tok_idx_out, n_keep_out, stream);
   else e = launch_select(pr.shape, pr.bp, gk, n_groups, ws.t, win_idx_out, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "select launch");
-  WKV_MARK(4)
+  WKV_MARK(3)
   e = launch_gather(pr.shape, lp, n_layers, gamma, tok_idx_out, n_keep_out, stream);
   if (e != hipSuccess) return hip_fail(e, "gather launch");
-  WKV_MARK(5)
+  WKV_MARK(4)
 #undef WKV_MARK
   return WKV_OK;
 }

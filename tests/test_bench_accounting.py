@@ -13,13 +13,28 @@ def test_c4_algorithmic_bytes():
     kept = 256 * 16 + 32                                    # rows kept per KV head
     gather_one_way = 32 * 2 * kept * 8 * row                # 32 layers, K and V
     assert ab["gather"] == 2 * gather_one_way == 1082130432
-    assert ab["score_pre"] == k_first + q
+    assert ab["score_stats"] == ab["score_stage"] == k_first + q          # Eq. 1-2 as a stage: the keys once
+    assert ab["score"] == k_first + q + 8 * 8 * 2046 * 4                  # + the window scores it writes
     assert ab["pipeline"] == k_first + q + 2 * gather_one_way == 1621098496
     # per layer group: 67.1 MB of keys + 67.6 MB gathered in + 67.6 MB out
     assert round(ab["pipeline"] / 8 / 1e6, 1) == 202.6
     assert bench.score_flops(w) == 2 * 32 * 32 * 128 * 32768 * 8
     # 60 % of the 8 TB/s peak on these bytes is the step time the target asks for
     assert abs(ab["pipeline"] / (0.6 * 8e12) * 1e6 - 337.7) < 0.1
+
+
+def test_traffic_figures_are_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    # a traffic profile counts only for the kernel sources it was measured on
+    import json, os
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    os.makedirs(tmp_path / "profiles")
+    rec = {"workloads": {"c4": {"kernel_sources_sha256": bench.kernel_sources_sha256(), "bytes_per_launch": {"gather": 1.0e9}}}}
+    (tmp_path / "profiles" / "traffic.json").write_text(json.dumps(rec))
+    assert bench.measured_traffic("c4") == {"gather": 1.0e9}
+    assert bench.measured_traffic("c2") == {}
+    rec["workloads"]["c4"]["kernel_sources_sha256"] = "0" * 64
+    (tmp_path / "profiles" / "traffic.json").write_text(json.dumps(rec))
+    assert bench.measured_traffic("c4") == {}
 
 
 def test_only_one_gpu_is_accepted():

@@ -665,7 +665,7 @@ def test_profiled_call_gives_the_same_results_and_sane_times(device):
     ms = call.profiled()
     torch.cuda.synchronize()
     assert len(ms) == W.WKV_N_STAGES == len(W.STAGE_NAMES)
-    assert all(0.0 <= x < 50.0 for x in ms) and ms[0] > 0.0 and ms[1] > 0.0 and ms[4] > 0.0, ms
+    assert all(0.0 < x < 50.0 for x in ms), ms
     for a, b in zip((st.win_idx, st.tok_idx, st.n_keep, *st.k_out, *st.v_out),
                     (ref.win_idx, ref.tok_idx, ref.n_keep, *ref.k_out, *ref.v_out)):
         assert torch.equal(a, b)
