@@ -345,6 +345,12 @@ def test_single_read_kernel_gives_up_and_the_two_pass_kernels_take_over(kw, devi
     assert torch.equal(ref.tok_idx, st.tok_idx) and torch.equal(ref.win_idx, st.win_idx)      # the very same kernels produced both
 
 
+def test_single_read_kernel_on_the_mixed_batch_at_full_size(device):
+    # c5 through the single-read kernel: 512 ragged rows of 16 .. 128 slices, ten rounds of the
+    # persistent grid; every problem against the oracle, the batched call's own window scores included
+    run_and_check(S.make_workload("c5"), device, n_gather_cpu=8, stage_groups=[2], flags=W.WKV_SCORE_SINGLE_READ)
+
+
 def test_single_read_and_two_pass_agree_at_full_size(device):
     w = S.make_workload("c4")
     a = P.DeviceState(w, device, flags=W.WKV_SCORE_SINGLE_READ); a.compress()
