@@ -124,6 +124,9 @@ void fill_shape(const wkv_problem *p, const wkv_dims &dims, Shape *s, BatchParam
     bp->seq[b].p = p->top_p[b] < p->win[b] ? p->top_p[b] : p->win[b];
     bp->seq[b].k = p->k_windows[b];
   }
+  for (int b = 0; b < WKV_MAX_BATCH; ++b) bp->by_length[b] = (uint8_t)b;
+  std::stable_sort(bp->by_length, bp->by_length + p->batch,
+                   [&](uint8_t a, uint8_t c) { return p->seq_len[a] < p->seq_len[c]; });
 }
 
 // Number of (row, chunk) work items that hold at least one key, for chunks of `chunk` keys.

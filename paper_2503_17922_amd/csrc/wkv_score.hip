@@ -228,10 +228,11 @@ __global__ __launch_bounds__(MF_THREADS * HV, HV == 1 ? 3 : 2) void score_mfma_k
   const int bx = PASS == 1 ? blockIdx.x : gridDim.x - 1 - blockIdx.x;
   const int bh = PASS == 1 ? blockIdx.y : gridDim.y - 1 - blockIdx.y;
   const int g = PASS == 1 ? blockIdx.z : gridDim.z - 1 - blockIdx.z;
-  const int b = bh / s.Hkv, h = bh % s.Hkv;
+  const int h = bh % s.Hkv;
+  const int b = PASS == 1 ? bp.by_length[bh / s.Hkv] : bh / s.Hkv;      // statistics: short sequences first
   const int L = bp.seq[b].L;
   const int n_review = L - s.w_obs;
-  const int64_t row = (int64_t)g * s.B * s.Hkv + bh;
+  const int64_t row = ((int64_t)g * s.B + b) * s.Hkv + h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = wave / MF_WAVES, kw = wave % MF_WAVES;   // row half, key tile slot of this wave
   const int col = lane & 15, quad = lane >> 4;
